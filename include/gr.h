@@ -1,0 +1,164 @@
+/*
+ * gr.h - C ABI of the MI355X (gfx950) generative-recommendation decode hot path.
+ *
+ * One decode step of beam-search item generation (xGR paper, arxiv 2512.11529) is
+ *   1. attention of all W beam queries of a request over a *separated* KV cache: one shared copy of
+ *      the prompt K/V per request plus W short per-beam decode caches (Sections 5.1, 5.2);
+ *   2. the beam item step: valid-item mask, log-softmax over valid tokens, cumulative beam score,
+ *      and the best W of the W*V candidates (Sections 6.1, 6.2), in fixed caller-owned buffers
+ *      (Section 6.3).
+ *
+ * Conventions for every entry point
+ *   - All data pointers are DEVICE pointers unless a comment says "host".  Parameter structs and
+ *     scalar arguments are host values read before the call returns.
+ *   - The caller owns every buffer, including workspaces and the mask blob.  The library never
+ *     allocates, frees or keeps device memory and holds no state between calls.
+ *   - gr_beam_attn and gr_beam_select only enqueue kernels on `stream` (a hipStream_t passed as
+ *     void*, NULL = default stream); they never synchronise.  gr_item_mask_build is a load-time
+ *     call and synchronises `stream` once to report table errors.
+ *   - Return value: GR_OK or a negative gr_status.  Nothing is printed, thrown or aborted.
+ *     Host-checkable argument errors are reported before anything is enqueued.
+ *   - bf16 tensors are raw 16-bit patterns; all tensors are dense, row-major, in the stated shape.
+ */
+#ifndef GR_H_
+#define GR_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int32_t gr_status;
+enum {
+  GR_OK = 0,
+  GR_ERR_INVALID_ARG = -1,        /* NULL pointer, non-positive size, step/u out of range, aliasing rule broken */
+  GR_ERR_UNSUPPORTED = -2,        /* shape outside what the kernels implement (see each call) */
+  GR_ERR_WORKSPACE_TOO_SMALL = -3,
+  GR_ERR_BAD_TABLE = -4,          /* item table unsorted, has duplicates, or a token outside [0, V) */
+  GR_ERR_HIP = -5                 /* a HIP runtime call or kernel launch failed */
+};
+
+/* Static description of a status code (host pointer, never NULL). */
+const char* gr_status_string(gr_status s);
+
+/* ------------------------------------------------------------------------------------------------
+ * gr_beam_attn - shared-prefix beam attention (Section 5.1 cache layout, Section 5.2 staging).
+ *
+ * For every request b, beam w and query head h (KV head h / (Hq/Hkv)) computes softmax attention of
+ * q[b,w,h,:] over the L_b prompt tokens of request b (stored ONCE, shared by all W beams) followed
+ * by that beam's own u decode tokens:
+ *     s_j = sm_scale * <q, k_j>,   out = sum_j softmax(s)_j v_j,   lse = log sum_j exp(s_j).
+ * The shared stage streams each prompt K/V tile once per workgroup for many beam queries (bf16
+ * MFMA, fp32 accumulation, online softmax); the unshared stage adds each beam's own tokens; the
+ * merge combines the (max, sum, output) partials.  No causal mask is applied: every key precedes
+ * or is the query position.
+ *
+ * Supported: d in {64, 128}; Hq % Hkv == 0; 1 <= u <= ND; L_b >= 0 (L_b + u >= 1).
+ * ------------------------------------------------------------------------------------------------ */
+typedef struct {
+  int32_t B, W, Hq, Hkv, d;   /* requests, beam width, query heads, KV heads, head dim              */
+  int32_t ND, u;              /* decode-token capacity per beam (Section 5.1: sized up front) and   */
+                              /* number of valid decode tokens this step                            */
+  int32_t max_L;              /* host copy of max_b L_b (sizes the launch; no device read-back)     */
+  int64_t total_L;            /* host copy of sum_b L_b = cu_seqlens[B]                             */
+  float   sm_scale;           /* softmax scale, normally 1/sqrt(d)                                  */
+  const void*    q;           /* bf16 [B, W, Hq, d]                                                 */
+  const void*    k_shared;    /* bf16 [total_L, Hkv, d]; request b = rows cu_seqlens[b]..[b+1]      */
+  const void*    v_shared;    /* bf16 [total_L, Hkv, d]                                             */
+  const int32_t* cu_seqlens;  /* int32 [B+1], non-decreasing, cu_seqlens[0] = 0                     */
+  const void*    k_unshared;  /* bf16 [B, W, ND, Hkv, d]; token slots [0, u) valid                  */
+  const void*    v_unshared;  /* bf16 [B, W, ND, Hkv, d]                                            */
+  void*          out;         /* bf16 [B, W, Hq, d]                                                 */
+  float*         lse_out;     /* fp32 [B, W, Hq] natural-log sum-exp of the scaled scores; or NULL  */
+} gr_attn_params;
+
+/* Bytes of workspace gr_beam_attn needs for these shapes (0 is possible).  Host only. */
+size_t gr_beam_attn_workspace_bytes(const gr_attn_params* p);
+
+/* Enqueue the attention.  `workspace` (device, 256-byte aligned) holds split-L partials; contents
+ * before and after the call are unspecified.  Errors: INVALID_ARG, UNSUPPORTED,
+ * WORKSPACE_TOO_SMALL, HIP. */
+gr_status gr_beam_attn(const gr_attn_params* p, void* workspace, size_t workspace_bytes, void* stream);
+
+/* ------------------------------------------------------------------------------------------------
+ * gr_item_mask_build - valid-item mask, built once at load time (Section 6.1: dense masks are
+ * pre-generated during model loading; the last level is kept in sparse form).
+ *
+ * Input: the table of valid items, int32 [n_items, depth], rows sorted lexicographically and
+ * distinct, tokens in [0, V).  Output: one position-independent device blob (offsets, no pointers;
+ * may be copied or saved) holding
+ *   level 0   bitmask of valid first tokens (V bits);
+ *   level 1   dense bitmask of valid second tokens per first token (V x V bits), plus the same
+ *             children in sparse CSR form and the table row range of every first token;
+ *   level 2   sparse: the third-token column of the table, addressed by row range.
+ * The blob is read-only for gr_beam_select and is shared by every step of every request.
+ *
+ * Supported: depth == 3; 1 <= V <= 32768; 1 <= n_items < 2^31.
+ * ------------------------------------------------------------------------------------------------ */
+size_t gr_item_mask_bytes(int64_t n_items, int32_t depth, int32_t V);
+size_t gr_item_mask_build_workspace_bytes(int64_t n_items, int32_t depth, int32_t V);
+
+/* items_sorted: device int32 [n_items, depth].  mask_out: device, 256-byte aligned, mask_bytes >=
+ * gr_item_mask_bytes().  Synchronises `stream`; returns GR_ERR_BAD_TABLE if the on-device check of
+ * order / distinctness / token range fails (mask_out is then unspecified). */
+gr_status gr_item_mask_build(const int32_t* items_sorted, int64_t n_items, int32_t depth, int32_t V,
+                             void* mask_out, size_t mask_bytes, void* workspace, size_t workspace_bytes,
+                             void* stream);
+
+/* ------------------------------------------------------------------------------------------------
+ * gr_beam_select - beam item step (Sections 6.1-6.3).
+ *
+ * For each request, for each live beam w (scores_in[w] > -inf) with logits x[v]:
+ *     valid(v) = some item starts with (prefix of w, v)                      (mask blob lookup)
+ *     m = max over valid x;  S = sum over valid exp(x - m) accumulated in fp64
+ *     lse = fp32(m + log S);  bias = scores_in[w] - lse;  cand[w*V+v] = bias + x[v]   (fp32 ops)
+ * and the W best candidates by (cand descending, flat index w*V+v ascending) are written, best
+ * first.  Selection stops reading as soon as the W survivors are fixed (threshold filtering
+ * instead of a sort of all W*V candidates - the early-termination idea of Section 6.2).
+ * Slots past the number of finite candidates are dead: parent = token = -1, score = -inf,
+ * prefix = -1, range = [0,0), item index = -1.
+ *
+ * Prefix state carried between steps (Section 6.3: fixed-size structures, overwritten in place by
+ * the caller swapping in/out buffers):
+ *   prefix  int32 [B, W, depth]  tokens chosen so far (entries >= step+1 are -1 on output)
+ *   range   int32 [B, W, 2]      table row range [lo, hi) of the prefix
+ * Step 0 ignores prefix_in/range_in.  Step 1 reads prefix_in[...,0]; step 2 reads range_in.
+ * Behaviour is undefined if logits or scores contain NaN, or if a live beam's prefix/range is not
+ * one this mask produced.
+ *
+ * mask == NULL: unconstrained (every token valid); range_out = [0,0), item_index_out = -1.
+ * Supported: depth == 3; 1 <= W <= 2048; 1 <= V <= 32768; W*V < 2^31.
+ * ------------------------------------------------------------------------------------------------ */
+enum {
+  GR_SELECT_FORCE_DENSE = 1     /* stream every live row in full even when a sparse gather would be cheaper */
+};
+
+typedef struct {
+  int32_t B, W, V, depth, step;   /* 0 <= step < depth                                              */
+  int32_t flags;                  /* GR_SELECT_* bits                                               */
+  const void*    mask;            /* blob from gr_item_mask_build (built for the same V, depth)     */
+  const float*   logits;          /* fp32 [B, W, V]                                                 */
+  const float*   scores_in;       /* fp32 [B, W]; -inf = dead beam                                  */
+  const int32_t* prefix_in;       /* int32 [B, W, depth]                                            */
+  const int32_t* range_in;        /* int32 [B, W, 2]                                                */
+  int32_t*       parent_out;      /* int32 [B, W] index of the beam each survivor extends           */
+  int32_t*       token_out;       /* int32 [B, W] token appended                                    */
+  float*         scores_out;      /* fp32 [B, W] cumulative log-probability, non-increasing         */
+  int32_t*       prefix_out;      /* int32 [B, W, depth]; must not alias prefix_in                  */
+  int32_t*       range_out;       /* int32 [B, W, 2];     must not alias range_in                   */
+  int32_t*       item_index_out;  /* int32 [B, W] table row of the finished item when step ==       */
+                                  /* depth-1 (else -1); may be NULL                                 */
+} gr_select_params;
+
+size_t gr_beam_select_workspace_bytes(int32_t B, int32_t W, int32_t V, int32_t depth);
+
+/* Enqueue the item step.  `workspace`: device, 256-byte aligned, contents unspecified before and
+ * after.  Errors: INVALID_ARG, UNSUPPORTED, WORKSPACE_TOO_SMALL, HIP. */
+gr_status gr_beam_select(const gr_select_params* p, void* workspace, size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GR_H_ */

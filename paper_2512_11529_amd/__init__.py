@@ -1,0 +1,211 @@
+"""MI355X (gfx950) hot path of a generative-recommendation decode step: thin binding over libgr.so.
+
+The three calls have the names and meaning of the C ABI in include/gr.h:
+
+    gr_beam_attn         shared-prefix beam attention over a separated KV cache
+    gr_item_mask_build   valid-item mask blob from the sorted item table (load time)
+    gr_beam_select       masked log-softmax + beam score accumulation + top-W selection
+
+This module only marshals arguments (torch CUDA tensors -> device pointers, current stream ->
+hipStream_t).  Every step of the path runs in the HIP kernels; there is no CPU or PyTorch fallback,
+and loading fails loudly when the library has not been built.
+"""
+import ctypes
+import os
+
+from . import build as _build
+
+__all__ = ["load_library", "gr_beam_attn", "gr_item_mask_build", "gr_beam_select", "gr_status_string",
+           "attn_workspace_bytes", "select_workspace_bytes", "GrError", "GR_SELECT_FORCE_DENSE", "LIB_PATH"]
+
+LIB_PATH = _build.LIB_PATH
+GR_SELECT_FORCE_DENSE = 1
+_lib = None
+
+
+class GrError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = int(status)
+        super().__init__(f"{where}: {gr_status_string(status)} ({int(status)})")
+
+
+class _AttnParams(ctypes.Structure):
+    _fields_ = [("B", ctypes.c_int32), ("W", ctypes.c_int32), ("Hq", ctypes.c_int32), ("Hkv", ctypes.c_int32),
+                ("d", ctypes.c_int32), ("ND", ctypes.c_int32), ("u", ctypes.c_int32), ("max_L", ctypes.c_int32),
+                ("total_L", ctypes.c_int64), ("sm_scale", ctypes.c_float),
+                ("q", ctypes.c_void_p), ("k_shared", ctypes.c_void_p), ("v_shared", ctypes.c_void_p),
+                ("cu_seqlens", ctypes.c_void_p), ("k_unshared", ctypes.c_void_p), ("v_unshared", ctypes.c_void_p),
+                ("out", ctypes.c_void_p), ("lse_out", ctypes.c_void_p)]
+
+
+class _SelectParams(ctypes.Structure):
+    _fields_ = [("B", ctypes.c_int32), ("W", ctypes.c_int32), ("V", ctypes.c_int32), ("depth", ctypes.c_int32),
+                ("step", ctypes.c_int32), ("flags", ctypes.c_int32),
+                ("mask", ctypes.c_void_p), ("logits", ctypes.c_void_p), ("scores_in", ctypes.c_void_p),
+                ("prefix_in", ctypes.c_void_p), ("range_in", ctypes.c_void_p), ("parent_out", ctypes.c_void_p),
+                ("token_out", ctypes.c_void_p), ("scores_out", ctypes.c_void_p), ("prefix_out", ctypes.c_void_p),
+                ("range_out", ctypes.c_void_p), ("item_index_out", ctypes.c_void_p)]
+
+
+def load_library(path: str = None):
+    """dlopen libgr.so and declare the C signatures.  Raises if the library is not built."""
+    global _lib
+    if _lib is not None and path is None:
+        return _lib
+    path = path or LIB_PATH
+    if not os.path.exists(path):
+        raise RuntimeError(f"{path} is missing: build it first (python -c 'import __graft_entry__ as g; g.build()')")
+    lib = ctypes.CDLL(path)
+    lib.gr_status_string.restype = ctypes.c_char_p
+    lib.gr_status_string.argtypes = [ctypes.c_int32]
+    lib.gr_beam_attn_workspace_bytes.restype = ctypes.c_size_t
+    lib.gr_beam_attn_workspace_bytes.argtypes = [ctypes.POINTER(_AttnParams)]
+    lib.gr_beam_attn.restype = ctypes.c_int32
+    lib.gr_beam_attn.argtypes = [ctypes.POINTER(_AttnParams), ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+    lib.gr_item_mask_bytes.restype = ctypes.c_size_t
+    lib.gr_item_mask_bytes.argtypes = [ctypes.c_int64, ctypes.c_int32, ctypes.c_int32]
+    lib.gr_item_mask_build_workspace_bytes.restype = ctypes.c_size_t
+    lib.gr_item_mask_build_workspace_bytes.argtypes = [ctypes.c_int64, ctypes.c_int32, ctypes.c_int32]
+    lib.gr_item_mask_build.restype = ctypes.c_int32
+    lib.gr_item_mask_build.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p,
+                                       ctypes.c_size_t, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+    lib.gr_beam_select_workspace_bytes.restype = ctypes.c_size_t
+    lib.gr_beam_select_workspace_bytes.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32]
+    lib.gr_beam_select.restype = ctypes.c_int32
+    lib.gr_beam_select.argtypes = [ctypes.POINTER(_SelectParams), ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+    _lib = lib
+    return lib
+
+
+def gr_status_string(status) -> str:
+    return load_library().gr_status_string(int(status)).decode()
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    import torch
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def _check(t, dtype, shape, name):
+    import torch
+    if not isinstance(t, torch.Tensor) or not t.is_cuda or not t.is_contiguous():
+        raise TypeError(f"{name}: expected a contiguous CUDA tensor")
+    if t.dtype != dtype:
+        raise TypeError(f"{name}: expected {dtype}, got {t.dtype}")
+    if shape is not None and tuple(t.shape) != tuple(shape):
+        raise ValueError(f"{name}: expected shape {tuple(shape)}, got {tuple(t.shape)}")
+
+
+def _attn_params(q, k_shared, v_shared, cu_seqlens, k_unshared, v_unshared, u, sm_scale, max_L, total_L, out, lse_out):
+    B, W, Hq, d = q.shape
+    Hkv = k_shared.shape[1]
+    ND = k_unshared.shape[2]
+    p = _AttnParams()
+    p.B, p.W, p.Hq, p.Hkv, p.d, p.ND, p.u = B, W, Hq, Hkv, d, ND, int(u)
+    p.max_L, p.total_L, p.sm_scale = int(max_L), int(total_L), float(sm_scale)
+    p.q, p.k_shared, p.v_shared = q.data_ptr(), k_shared.data_ptr(), v_shared.data_ptr()
+    p.cu_seqlens, p.k_unshared, p.v_unshared = cu_seqlens.data_ptr(), k_unshared.data_ptr(), v_unshared.data_ptr()
+    p.out = out.data_ptr() if out is not None else None
+    p.lse_out = lse_out.data_ptr() if lse_out is not None else None
+    return p
+
+
+def attn_workspace_bytes(B, W, Hq, Hkv, d, max_L) -> int:
+    p = _AttnParams()
+    p.B, p.W, p.Hq, p.Hkv, p.d, p.max_L = B, W, Hq, Hkv, d, int(max_L)
+    return int(load_library().gr_beam_attn_workspace_bytes(ctypes.byref(p)))
+
+
+def gr_beam_attn(q, k_shared, v_shared, cu_seqlens, k_unshared, v_unshared, u, sm_scale, max_L, total_L,
+                 out=None, lse_out=None, workspace=None, stream=None):
+    """Shared-prefix beam attention.  bf16 CUDA tensors: q [B,W,Hq,d], k/v_shared [total_L,Hkv,d],
+    k/v_unshared [B,W,ND,Hkv,d]; cu_seqlens int32 [B+1].  max_L / total_L are host integers.
+    Returns (out bf16 [B,W,Hq,d], lse fp32 [B,W,Hq] or None).  Enqueues on `stream` (default: current)."""
+    import torch
+    lib = load_library()
+    B, W, Hq, d = q.shape
+    _check(q, torch.bfloat16, None, "q")
+    _check(k_shared, torch.bfloat16, (k_shared.shape[0], k_shared.shape[1], d), "k_shared")
+    _check(v_shared, torch.bfloat16, tuple(k_shared.shape), "v_shared")
+    _check(cu_seqlens, torch.int32, (B + 1,), "cu_seqlens")
+    _check(k_unshared, torch.bfloat16, (B, W, k_unshared.shape[2], k_shared.shape[1], d), "k_unshared")
+    _check(v_unshared, torch.bfloat16, tuple(k_unshared.shape), "v_unshared")
+    if k_shared.shape[0] < int(total_L):
+        raise ValueError("k_shared has fewer rows than total_L")
+    if out is None:
+        out = torch.empty_like(q)
+    _check(out, torch.bfloat16, tuple(q.shape), "out")
+    if lse_out is not None:
+        _check(lse_out, torch.float32, (B, W, Hq), "lse_out")
+    p = _attn_params(q, k_shared, v_shared, cu_seqlens, k_unshared, v_unshared, u, sm_scale, max_L, total_L, out, lse_out)
+    need = int(lib.gr_beam_attn_workspace_bytes(ctypes.byref(p)))
+    if workspace is None and need > 0:
+        workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    rc = lib.gr_beam_attn(ctypes.byref(p), _ptr(workspace), ws_bytes, _stream(stream))
+    if rc != 0:
+        raise GrError(rc, "gr_beam_attn")
+    return out, lse_out
+
+
+def gr_item_mask_build(items_sorted, V, stream=None):
+    """Build the mask blob from a sorted, distinct int32 CUDA table [N, 3].  Returns a uint8 CUDA tensor."""
+    import torch
+    lib = load_library()
+    _check(items_sorted, torch.int32, None, "items_sorted")
+    N, depth = items_sorted.shape
+    nbytes = int(lib.gr_item_mask_bytes(N, depth, int(V)))
+    if nbytes == 0:
+        raise GrError(-2, "gr_item_mask_bytes")
+    blob = torch.empty(nbytes, dtype=torch.uint8, device=items_sorted.device)
+    ws = torch.empty(int(lib.gr_item_mask_build_workspace_bytes(N, depth, int(V))), dtype=torch.uint8, device=items_sorted.device)
+    rc = lib.gr_item_mask_build(_ptr(items_sorted), N, depth, int(V), _ptr(blob), nbytes, _ptr(ws), ws.numel(), _stream(stream))
+    if rc != 0:
+        raise GrError(rc, "gr_item_mask_build")
+    return blob
+
+
+def select_workspace_bytes(B, W, V, depth) -> int:
+    return int(load_library().gr_beam_select_workspace_bytes(B, W, V, depth))
+
+
+def gr_beam_select(mask, logits, scores_in, prefix_in, range_in, step, flags=0, out=None, workspace=None, stream=None):
+    """Beam item step.  logits fp32 [B,W,V]; scores_in fp32 [B,W]; prefix_in int32 [B,W,depth]; range_in int32
+    [B,W,2]; mask = blob from gr_item_mask_build or None.  `out` may hold preallocated tensors under the keys
+    parent, token, scores, prefix, range, item_index.  Returns that dict.  Enqueues on `stream`."""
+    import torch
+    lib = load_library()
+    B, W, V = logits.shape
+    depth = prefix_in.shape[2]
+    _check(logits, torch.float32, None, "logits")
+    _check(scores_in, torch.float32, (B, W), "scores_in")
+    _check(prefix_in, torch.int32, (B, W, depth), "prefix_in")
+    _check(range_in, torch.int32, (B, W, 2), "range_in")
+    dev = logits.device
+    if out is None:
+        out = {}
+    spec = dict(parent=((B, W), torch.int32), token=((B, W), torch.int32), scores=((B, W), torch.float32),
+                prefix=((B, W, depth), torch.int32), range=((B, W, 2), torch.int32), item_index=((B, W), torch.int32))
+    for k, (shape, dt) in spec.items():
+        if k not in out or out[k] is None:
+            out[k] = torch.empty(shape, dtype=dt, device=dev)
+        _check(out[k], dt, shape, k)
+    need = int(lib.gr_beam_select_workspace_bytes(B, W, V, depth))
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=dev)
+    p = _SelectParams()
+    p.B, p.W, p.V, p.depth, p.step, p.flags = B, W, V, depth, int(step), int(flags)
+    p.mask = mask.data_ptr() if mask is not None else None
+    p.logits, p.scores_in = logits.data_ptr(), scores_in.data_ptr()
+    p.prefix_in, p.range_in = prefix_in.data_ptr(), range_in.data_ptr()
+    p.parent_out, p.token_out, p.scores_out = out["parent"].data_ptr(), out["token"].data_ptr(), out["scores"].data_ptr()
+    p.prefix_out, p.range_out, p.item_index_out = out["prefix"].data_ptr(), out["range"].data_ptr(), out["item_index"].data_ptr()
+    rc = lib.gr_beam_select(ctypes.byref(p), _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream))
+    if rc != 0:
+        raise GrError(rc, "gr_beam_select")
+    return out

@@ -1,0 +1,436 @@
+// gr_beam_attn: shared-prefix beam attention on gfx950 (paper Sections 5.1, 5.2).
+//
+// Work unit = (request b, KV head h, block of query rows, L segment).  The W*g query rows that share
+// KV head h of request b (g = Hq/Hkv) form the N side of a transposed score matrix
+//     S^T[kv, q] = K[kv, :] . Q[q, :]          (v_mfma_f32_32x32x16_bf16, A = K tile from LDS, B = Q in registers)
+// so that every lane owns ONE query column: the online-softmax max / sum / rescale are per-lane
+// scalars and the exponentiated scores leave the accumulators already in the B-operand layout of
+//     O^T[d, q] += V^T[d, kv] . P^T[kv, q]     (A = V tile read from LDS with the transposing ds_read_b64_tr_b16).
+// Each prompt K/V tile is staged once per workgroup (coalesced 16-byte loads -> padded LDS) and used
+// by all query rows of the block.  The unshared stage (each beam's own u decode tokens) and the merge
+// run in the epilogue of segment 0 on the same per-lane state; when the prompt is split into
+// segments, partial (max, sum, O) go to the workspace and k_attn_merge combines them.
+#include "gr_internal.hpp"
+
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+
+constexpr int KT = 64;        // kv tokens per LDS tile
+constexpr int PAD = 16;       // bf16 elements of row padding (32 B): conflict-free b128 and tr-b64 reads
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+struct AttnCtx {
+  int B, W, Hq, Hkv, g, ND, u;
+  int M;            // W * g query rows per (b, kv head)
+  int MB;           // row blocks per (b, kv head)
+  int nsplit;       // L segments per request
+  int n_groups;     // B * Hkv * nsplit
+  float c;          // sm_scale * log2(e)
+  const uint16_t* q;
+  const uint16_t* ks;
+  const uint16_t* vs;
+  const int32_t* cu;
+  const uint16_t* ku;
+  const uint16_t* vu;
+  uint16_t* out;
+  float* lse;
+  float* part_o;    // [B, nsplit, W*Hq, D] fp32, unnormalised
+  float* part_ml;   // [B, nsplit, W*Hq, 2] (max in log2 domain, sum)
+};
+
+__device__ __forceinline__ float bf16_bits_to_float(uint32_t h) { return __uint_as_float(h << 16); }
+
+__device__ __forceinline__ bf16x8 as_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8, v); }
+
+template <int D, int NCB, int NWAVES>
+__global__ void __launch_bounds__(NWAVES * 64) k_beam_attn(AttnCtx c) {
+  constexpr int NT = NWAVES * 64;
+  constexpr int MWG = NWAVES * 32 * NCB;
+  constexpr int LDS_STRIDE = D + PAD;            // bf16 elements per LDS row
+  constexpr int PIECES = KT * D / 8;             // 16-byte pieces per tile
+  constexpr int PPT = PIECES / NT;               // pieces per thread
+  constexpr int PPR = D / 8;                     // pieces per row
+  static_assert(PIECES % NT == 0, "tile must divide over the threads");
+  __shared__ __attribute__((aligned(16))) uint16_t s_k[KT * LDS_STRIDE];
+  __shared__ __attribute__((aligned(16))) uint16_t s_v[KT * LDS_STRIDE];
+
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, G = lane >> 5, n32 = lane & 31;
+
+  // XCD-aware unit order: workgroups are dealt round-robin to the 8 XCDs, so ids congruent mod 8
+  // share an L2.  The MB row blocks that read the same K/V stream get consecutive slots of one XCD.
+  const int id = blockIdx.x;
+  const int xcd = id & 7, slot = id >> 3;
+  const int group = (slot / c.MB) * 8 + xcd;
+  const int mbi = slot % c.MB;
+  if (group >= c.n_groups) return;
+  const int sp = group % c.nsplit;
+  const int kvh = (group / c.nsplit) % c.Hkv;
+  const int b = group / (c.nsplit * c.Hkv);
+
+  const int row0 = c.cu[b];
+  const int Lb = c.cu[b + 1] - row0;
+  int chunk = (Lb + c.nsplit - 1) / c.nsplit;
+  chunk = ((chunk + KT - 1) / KT) * KT;
+  const int seg0 = min(Lb, sp * chunk), seg1 = min(Lb, seg0 + chunk);
+  const int ntiles = (seg1 - seg0 + KT - 1) / KT;
+
+  // ---- Q as B operands: lane holds query column n32 of block cb, d = 16*ks + 8*G + (0..7)
+  bf16x8 qop[NCB][D / 16];
+  int qrow[NCB];       // local query row or -1
+#pragma unroll
+  for (int cb = 0; cb < NCB; cb++) {
+    const int r = mbi * MWG + wave * 32 * NCB + cb * 32 + n32;
+    qrow[cb] = (r < c.M) ? r : -1;
+    const int w = r / c.g, j = r % c.g;
+    const uint16_t* qp = c.q + (((size_t)b * c.W + w) * c.Hq + kvh * c.g + j) * D + G * 8;
+#pragma unroll
+    for (int ks = 0; ks < D / 16; ks++) {
+      uint4 v = make_uint4(0, 0, 0, 0);
+      if (r < c.M) v = *(const uint4*)(qp + ks * 16);
+      qop[cb][ks] = as_bf16x8(v);
+    }
+  }
+
+  f32x16 o_acc[D / 32][NCB];
+#pragma unroll
+  for (int db = 0; db < D / 32; db++)
+#pragma unroll
+    for (int cb = 0; cb < NCB; cb++)
+#pragma unroll
+      for (int i = 0; i < 16; i++) o_acc[db][cb][i] = 0.f;
+  float m_run[NCB], l_run[NCB];
+#pragma unroll
+  for (int cb = 0; cb < NCB; cb++) { m_run[cb] = -INFINITY; l_run[cb] = 0.f; }
+
+  // ---- K/V tile staging
+  const uint16_t* kbase = c.ks + ((size_t)row0 * c.Hkv + kvh) * D;
+  const uint16_t* vbase = c.vs + ((size_t)row0 * c.Hkv + kvh) * D;
+  const size_t tok_stride = (size_t)c.Hkv * D;
+  uint4 kreg[PPT], vreg[PPT];
+  auto load_tile = [&](int t) {
+    const int tok0 = seg0 + t * KT;
+#pragma unroll
+    for (int i = 0; i < PPT; i++) {
+      const int p = tid + i * NT;
+      const int r = p / PPR, col = (p % PPR) * 8;
+      const int tok = tok0 + r;
+      uint4 kv = make_uint4(0, 0, 0, 0), vv = make_uint4(0, 0, 0, 0);
+      if (tok < seg1) {
+        kv = *(const uint4*)(kbase + (size_t)tok * tok_stride + col);
+        vv = *(const uint4*)(vbase + (size_t)tok * tok_stride + col);
+      }
+      kreg[i] = kv;
+      vreg[i] = vv;
+    }
+  };
+  auto store_tile = [&]() {
+#pragma unroll
+    for (int i = 0; i < PPT; i++) {
+      const int p = tid + i * NT;
+      const int r = p / PPR, col = (p % PPR) * 8;
+      *(uint4*)(&s_k[r * LDS_STRIDE + col]) = kreg[i];
+      *(uint4*)(&s_v[r * LDS_STRIDE + col]) = vreg[i];
+    }
+  };
+
+  if (ntiles > 0) load_tile(0);
+  for (int t = 0; t < ntiles; t++) {
+    __syncthreads();
+    store_tile();
+    __syncthreads();
+    if (t + 1 < ntiles) load_tile(t + 1);
+
+    // ---- S^T = K . Q^T for the 64-token tile: two 32-token sub-tiles x NCB column blocks
+    f32x16 s_acc[KT / 32][NCB];
+#pragma unroll
+    for (int sub = 0; sub < KT / 32; sub++)
+#pragma unroll
+      for (int cb = 0; cb < NCB; cb++)
+#pragma unroll
+        for (int i = 0; i < 16; i++) s_acc[sub][cb][i] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < D / 16; ks++) {
+#pragma unroll
+      for (int sub = 0; sub < KT / 32; sub++) {
+        const bf16x8 a = as_bf16x8(*(const uint4*)(&s_k[(sub * 32 + n32) * LDS_STRIDE + ks * 16 + G * 8]));
+#pragma unroll
+        for (int cb = 0; cb < NCB; cb++)
+          s_acc[sub][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qop[cb][ks], s_acc[sub][cb], 0, 0, 0);
+      }
+    }
+    // tokens past the end of the segment do not exist
+    const int tok0 = seg0 + t * KT;
+    if (tok0 + KT > seg1) {
+#pragma unroll
+      for (int sub = 0; sub < KT / 32; sub++)
+#pragma unroll
+        for (int i = 0; i < 16; i++) {
+          const int kv = tok0 + sub * 32 + 8 * (i / 4) + 4 * G + (i % 4);
+          if (kv >= seg1) {
+#pragma unroll
+            for (int cb = 0; cb < NCB; cb++) s_acc[sub][cb][i] = -INFINITY;
+          }
+        }
+    }
+
+    // ---- online softmax, one query column per lane (the other half of the column is in lane^32)
+    bf16x8 pop[KT / 16][NCB];
+#pragma unroll
+    for (int cb = 0; cb < NCB; cb++) {
+      float mx = s_acc[0][cb][0];
+#pragma unroll
+      for (int sub = 0; sub < KT / 32; sub++)
+#pragma unroll
+        for (int i = 0; i < 16; i++) mx = fmaxf(mx, s_acc[sub][cb][i]);
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      const float m_new = fmaxf(m_run[cb], mx);
+      const float alpha = __builtin_amdgcn_exp2f((m_run[cb] - m_new) * c.c);
+      const float mc = m_new * c.c;
+      float rs = 0.f;
+#pragma unroll
+      for (int sub = 0; sub < KT / 32; sub++)
+#pragma unroll
+        for (int i = 0; i < 16; i++) {
+          const float p = __builtin_amdgcn_exp2f(fmaf(s_acc[sub][cb][i], c.c, -mc));
+          s_acc[sub][cb][i] = p;
+          rs += p;
+        }
+      l_run[cb] = l_run[cb] * alpha + rs;
+      m_run[cb] = m_new;
+      if (__any(alpha != 1.0f)) {
+#pragma unroll
+        for (int db = 0; db < D / 32; db++)
+#pragma unroll
+          for (int i = 0; i < 16; i++) o_acc[db][cb][i] *= alpha;
+      }
+      // P^T as B operands: slab s = accumulator registers 8*(s%2) .. +7 of sub-tile s/2
+#pragma unroll
+      for (int s = 0; s < KT / 16; s++) {
+        bf16x8 pv;
+#pragma unroll
+        for (int e = 0; e < 8; e += 2) {
+          f32x2 two = {s_acc[s / 2][cb][8 * (s % 2) + e], s_acc[s / 2][cb][8 * (s % 2) + e + 1]};
+          bf16x2 h = __builtin_convertvector(two, bf16x2);
+          pv[e] = h[0];
+          pv[e + 1] = h[1];
+        }
+        pop[s][cb] = pv;
+      }
+    }
+
+    // ---- O^T += V^T . P^T.  V^T operand: d = 32*db + (lane%32), k slot e <-> token 16*s + 8*(e/4) + 4*G + e%4
+#pragma unroll
+    for (int s = 0; s < KT / 16; s++) {
+#pragma unroll
+      for (int db = 0; db < D / 32; db++) {
+        const int vrow = s * 16 + 4 * G + ((lane & 15) >> 2);
+        const int vcol = db * 32 + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+        const uint16_t* p0 = &s_v[vrow * LDS_STRIDE + vcol];
+        s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p0));
+        s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p0 + 8 * LDS_STRIDE));
+        typedef short s16x8 __attribute__((ext_vector_type(8)));
+        s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        const bf16x8 a = __builtin_bit_cast(bf16x8, both);
+#pragma unroll
+        for (int cb = 0; cb < NCB; cb++)
+          o_acc[db][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pop[s][cb], o_acc[db][cb], 0, 0, 0);
+      }
+    }
+  }
+
+  // ---- epilogue: unshared stage + merge (segment 0), then normalise or write partials
+#pragma unroll
+  for (int cb = 0; cb < NCB; cb++) {
+    const int r = qrow[cb];
+    if (r < 0) continue;
+    const int w = r / c.g, j = r % c.g;
+    const int hq = kvh * c.g + j;
+    float m = m_run[cb], l = l_run[cb];
+    if (sp == 0) {
+      for (int ju = 0; ju < c.u; ju++) {
+        const size_t off = ((((size_t)b * c.W + w) * c.ND + ju) * c.Hkv + kvh) * D;
+        const uint16_t* kp = c.ku + off + G * 8;
+        float dot = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < D / 16; ks++) {
+          const uint4 kv = *(const uint4*)(kp + ks * 16);
+          const uint32_t kw[4] = {kv.x, kv.y, kv.z, kv.w};
+#pragma unroll
+          for (int e = 0; e < 4; e++) {
+            dot = fmaf((float)qop[cb][ks][2 * e], bf16_bits_to_float(kw[e] & 0xffffu), dot);
+            dot = fmaf((float)qop[cb][ks][2 * e + 1], bf16_bits_to_float(kw[e] >> 16), dot);
+          }
+        }
+        dot += __shfl_xor(dot, 32, 64);
+        const float m_new = fmaxf(m, dot);
+        const float alpha = __builtin_amdgcn_exp2f((m - m_new) * c.c);
+        const float p = __builtin_amdgcn_exp2f((dot - m_new) * c.c);
+        l = l * alpha + (G == 0 ? p : 0.f);
+        m = m_new;
+        const uint16_t* vp = c.vu + off + 4 * G;
+#pragma unroll
+        for (int db = 0; db < D / 32; db++)
+#pragma unroll
+          for (int q4 = 0; q4 < 4; q4++) {
+            const uint2 vv = *(const uint2*)(vp + db * 32 + 8 * q4);
+            const float v0 = bf16_bits_to_float(vv.x & 0xffffu), v1 = bf16_bits_to_float(vv.x >> 16);
+            const float v2 = bf16_bits_to_float(vv.y & 0xffffu), v3 = bf16_bits_to_float(vv.y >> 16);
+            o_acc[db][cb][4 * q4 + 0] = fmaf(p, v0, o_acc[db][cb][4 * q4 + 0] * alpha);
+            o_acc[db][cb][4 * q4 + 1] = fmaf(p, v1, o_acc[db][cb][4 * q4 + 1] * alpha);
+            o_acc[db][cb][4 * q4 + 2] = fmaf(p, v2, o_acc[db][cb][4 * q4 + 2] * alpha);
+            o_acc[db][cb][4 * q4 + 3] = fmaf(p, v3, o_acc[db][cb][4 * q4 + 3] * alpha);
+          }
+      }
+    }
+    const float l_tot = l + __shfl_xor(l, 32, 64);
+    const size_t orow = ((size_t)b * c.W + w) * c.Hq + hq;
+    if (c.nsplit == 1) {
+      const float inv = (l_tot > 0.f) ? 1.0f / l_tot : 0.f;
+      uint16_t* op = c.out + orow * D + 4 * G;
+#pragma unroll
+      for (int db = 0; db < D / 32; db++)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; q4++) {
+          f32x2 a = {o_acc[db][cb][4 * q4] * inv, o_acc[db][cb][4 * q4 + 1] * inv};
+          f32x2 bb = {o_acc[db][cb][4 * q4 + 2] * inv, o_acc[db][cb][4 * q4 + 3] * inv};
+          bf16x2 ha = __builtin_convertvector(a, bf16x2), hb = __builtin_convertvector(bb, bf16x2);
+          uint2 st;
+          st.x = __builtin_bit_cast(uint32_t, ha);
+          st.y = __builtin_bit_cast(uint32_t, hb);
+          *(uint2*)(op + db * 32 + 8 * q4) = st;
+        }
+      if (c.lse && G == 0) c.lse[orow] = (l_tot > 0.f) ? (m * c.c + __builtin_amdgcn_logf(l_tot)) * kLn2 : -INFINITY;
+    } else {
+      const size_t prow = ((size_t)b * c.nsplit + sp) * ((size_t)c.W * c.Hq) + (size_t)w * c.Hq + hq;
+      float* pp = c.part_o + prow * D + 4 * G;
+#pragma unroll
+      for (int db = 0; db < D / 32; db++)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; q4++) {
+          f32x4 st = {o_acc[db][cb][4 * q4], o_acc[db][cb][4 * q4 + 1], o_acc[db][cb][4 * q4 + 2], o_acc[db][cb][4 * q4 + 3]};
+          *(f32x4*)(pp + db * 32 + 8 * q4) = st;
+        }
+      if (G == 0) {
+        f32x2 ml = {(l_tot > 0.f) ? m * c.c : -INFINITY, l_tot};
+        *(f32x2*)(c.part_ml + prow * 2) = ml;
+      }
+    }
+  }
+}
+
+// Merge of the per-segment partials (Section 5.2 merge stage): one wave per output row.
+template <int D>
+__global__ void __launch_bounds__(256) k_attn_merge(AttnCtx c) {
+  const int lane = threadIdx.x & 63;
+  const size_t row = (size_t)blockIdx.x * 4 + (threadIdx.x >> 6);   // (b, w, hq) flattened
+  const size_t rows_per_b = (size_t)c.W * c.Hq;
+  if (row >= (size_t)c.B * rows_per_b) return;
+  const size_t b = row / rows_per_b, rr = row % rows_per_b;
+  float M2 = -INFINITY;
+  for (int s = 0; s < c.nsplit; s++) M2 = fmaxf(M2, c.part_ml[((b * c.nsplit + s) * rows_per_b + rr) * 2]);
+  float L = 0.f;
+  float acc[D / 64];
+#pragma unroll
+  for (int k = 0; k < D / 64; k++) acc[k] = 0.f;
+  for (int s = 0; s < c.nsplit; s++) {
+    const size_t prow = (b * c.nsplit + s) * rows_per_b + rr;
+    const float m2 = c.part_ml[prow * 2], l = c.part_ml[prow * 2 + 1];
+    if (!(l > 0.f)) continue;
+    const float sc = __builtin_amdgcn_exp2f(m2 - M2);
+    L += l * sc;
+#pragma unroll
+    for (int k = 0; k < D / 64; k++) acc[k] += c.part_o[prow * D + k * 64 + lane] * sc;
+  }
+  const float inv = (L > 0.f) ? 1.0f / L : 0.f;
+#pragma unroll
+  for (int k = 0; k < D / 64; k++) {
+    const __bf16 h = (__bf16)(acc[k] * inv);
+    c.out[row * D + k * 64 + lane] = __builtin_bit_cast(uint16_t, h);
+  }
+  if (c.lse && lane == 0) c.lse[row] = (L > 0.f) ? (M2 + __builtin_amdgcn_logf(L)) * kLn2 : -INFINITY;
+}
+
+constexpr int kNCB = 2, kNWaves = 4;
+constexpr int kMWG = kNWaves * 32 * kNCB;
+
+int choose_nsplit(const gr_attn_params* p) {
+  const int g = p->Hq / p->Hkv;
+  const int MB = (p->W * g + kMWG - 1) / kMWG;
+  const int64_t units = (int64_t)p->B * p->Hkv * MB;
+  if (units >= 512 || p->max_L <= 4 * KT) return 1;
+  int64_t want = (1024 + units - 1) / units;
+  int64_t cap = p->max_L / (4 * KT);     // at least four tiles per segment
+  int64_t n = want < cap ? want : cap;
+  if (n > 16) n = 16;
+  if (n < 1) n = 1;
+  return (int)n;
+}
+
+}  // namespace
+
+extern "C" size_t gr_beam_attn_workspace_bytes(const gr_attn_params* p) {
+  if (!p || p->B <= 0 || p->W <= 0 || p->Hq <= 0 || p->Hkv <= 0 || p->Hq % p->Hkv) return 0;
+  const int ns = choose_nsplit(p);
+  if (ns == 1) return 0;
+  const size_t rows = (size_t)p->B * ns * p->W * p->Hq;
+  return gr_align256(rows * p->d * 4) + gr_align256(rows * 8);
+}
+
+extern "C" gr_status gr_beam_attn(const gr_attn_params* p, void* workspace, size_t workspace_bytes, void* stream_) {
+  hipStream_t stream = (hipStream_t)stream_;
+  if (!p) return GR_ERR_INVALID_ARG;
+  if (p->B <= 0 || p->W <= 0 || p->Hq <= 0 || p->Hkv <= 0 || p->d <= 0 || p->ND < 0 || p->u < 0 || p->u > p->ND)
+    return GR_ERR_INVALID_ARG;
+  if (p->max_L < 0 || p->total_L < 0 || p->total_L > (int64_t)p->max_L * p->B) return GR_ERR_INVALID_ARG;
+  if (!p->q || !p->cu_seqlens || !p->out) return GR_ERR_INVALID_ARG;
+  if (p->total_L > 0 && (!p->k_shared || !p->v_shared)) return GR_ERR_INVALID_ARG;
+  if (p->u > 0 && (!p->k_unshared || !p->v_unshared)) return GR_ERR_INVALID_ARG;
+  if (p->Hq % p->Hkv) return GR_ERR_INVALID_ARG;
+  if (p->d != 64 && p->d != 128) return GR_ERR_UNSUPPORTED;
+  if (p->total_L >= ((int64_t)1 << 31)) return GR_ERR_UNSUPPORTED;
+  const int g = p->Hq / p->Hkv;
+  if ((int64_t)p->W * g >= ((int64_t)1 << 30)) return GR_ERR_UNSUPPORTED;
+
+  AttnCtx c;
+  c.B = p->B; c.W = p->W; c.Hq = p->Hq; c.Hkv = p->Hkv; c.g = g; c.ND = p->ND; c.u = p->u;
+  c.M = p->W * g;
+  c.MB = (c.M + kMWG - 1) / kMWG;
+  c.nsplit = choose_nsplit(p);
+  c.n_groups = p->B * p->Hkv * c.nsplit;
+  c.c = p->sm_scale * kLog2e;
+  c.q = (const uint16_t*)p->q; c.ks = (const uint16_t*)p->k_shared; c.vs = (const uint16_t*)p->v_shared;
+  c.cu = p->cu_seqlens; c.ku = (const uint16_t*)p->k_unshared; c.vu = (const uint16_t*)p->v_unshared;
+  c.out = (uint16_t*)p->out; c.lse = p->lse_out;
+  c.part_o = nullptr; c.part_ml = nullptr;
+  if (c.nsplit > 1) {
+    const size_t need = gr_beam_attn_workspace_bytes(p);
+    if (!workspace || ((uintptr_t)workspace & 255)) return GR_ERR_INVALID_ARG;
+    if (workspace_bytes < need) return GR_ERR_WORKSPACE_TOO_SMALL;
+    const size_t rows = (size_t)p->B * c.nsplit * p->W * p->Hq;
+    c.part_o = (float*)workspace;
+    c.part_ml = (float*)((char*)workspace + gr_align256(rows * p->d * 4));
+  }
+  const int64_t groups_padded = ((int64_t)c.n_groups + 7) / 8 * 8;
+  const int64_t grid = groups_padded * c.MB;
+  if (grid >= ((int64_t)1 << 31)) return GR_ERR_UNSUPPORTED;
+  if (p->d == 128)
+    hipLaunchKernelGGL((k_beam_attn<128, kNCB, kNWaves>), dim3((unsigned)grid), dim3(kNWaves * 64), 0, stream, c);
+  else
+    hipLaunchKernelGGL((k_beam_attn<64, kNCB, kNWaves>), dim3((unsigned)grid), dim3(kNWaves * 64), 0, stream, c);
+  if (c.nsplit > 1) {
+    const int64_t rows = (int64_t)p->B * p->W * p->Hq;
+    const unsigned mgrid = (unsigned)((rows + 3) / 4);
+    if (p->d == 128) hipLaunchKernelGGL((k_attn_merge<128>), dim3(mgrid), dim3(256), 0, stream, c);
+    else hipLaunchKernelGGL((k_attn_merge<64>), dim3(mgrid), dim3(256), 0, stream, c);
+  }
+  GR_HIP_TRY(hipGetLastError());
+  return GR_OK;
+}
