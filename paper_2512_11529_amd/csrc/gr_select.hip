@@ -1,12 +1,19 @@
 // gr_beam_select: beam item step (paper Sections 6.1-6.3) on gfx950.
 //
-// Two kernels per call, no host synchronisation, no allocation:
-//   k_row_stats     one workgroup per beam row: valid set from the mask blob, max / fp64 sum-exp over
-//                   valid tokens, lse and the row's additive bias (score_in - lse).
-//   k_select        one workgroup per request: exact top-W of the request's candidates by
-//                   (score descending, flat index ascending) using an MSB radix select on a 64-bit
-//                   composite key that stops as soon as the survivors fit in LDS, then a bitonic sort
-//                   of the survivors and the write-out of the new beam state.
+// Kernels per call (no host synchronisation, no allocation; everything lives in caller buffers):
+//   k_row_dense    one workgroup per beam row that is streamed in full: validity bits staged in LDS
+//                  (dense level-0 / level-1 mask rows, or the row's sparse last-level positions set
+//                  in an empty mask), logits read ONCE with 16-byte loads and kept in registers for
+//                  the max, the fp64 sum-exp and the per-chunk maxima.
+//   k_row_sparse   one wavefront per beam row with few valid children: gathers only those logits.
+//   k_select       one workgroup per request: top-W of the request's candidates by (score descending,
+//                  flat index ascending).  It never sorts the W*V candidates: the rows kernels leave
+//                  one "chunk key" (best candidate score) per 1/256th of a row; a histogram of those
+//                  keys yields a threshold that at least W candidates reach, only the chunks that
+//                  reach it are re-read, and only their candidates above the threshold are sorted
+//                  (the early-termination idea of Section 6.2: stop as soon as the survivors are
+//                  fixed).  If the survivors do not fit in LDS (massive ties) an exact MSB radix
+//                  select over all candidates takes over.
 //
 // Arithmetic that decides beam order is fixed: m = fp32 max over valid logits, S = fp64 sum of
 // exp(x - m), lse = fp32(m + log S), bias = score_in - lse (fp32), cand = bias + x (fp32), with no
@@ -16,13 +23,22 @@
 namespace {
 
 constexpr int kRowThreads = 256;
+constexpr int kChunksPerRow = 256;  // chunk keys stored per row (dense rows use all, sparse rows the first 64)
 constexpr int kSelThreads = 1024;
 constexpr int kSparseMax = 256;     // rows with at most this many valid children are gathered, not streamed
-constexpr int kListCap = 4096;      // survivors that fit in LDS
+constexpr int kListCap = 8192;      // survivors that fit in LDS
+constexpr int kChunkCap = 2048;     // chunks re-read by the fast path
+constexpr int kHistBins = 2048;
 constexpr int kMaxMaskWords = 1024; // V <= 32768
+constexpr int kRegV4 = 8;           // float4 per thread kept in registers (V <= 8192)
+constexpr size_t kSelLdsBytes = (size_t)kListCap * 8 + (size_t)kHistBins * 4 + (size_t)kChunkCap * 4;
+
+enum { ROW_DEAD = 0, ROW_DENSE = 1, ROW_SPARSE = 2 };
 
 struct SelCtx {
   int B, W, V, depth, step, flags;
+  int vec4;                  // V % 4 == 0: rows are 16-byte aligned, chunks interleave float4 groups
+  int epc;                   // element slots per chunk of a dense row
   const char* blob;          // mask blob or nullptr
   const float* logits;
   const float* scores_in;
@@ -35,7 +51,9 @@ struct SelCtx {
   int32_t* range_out;
   int32_t* item_index_out;
   float* row_bias;           // workspace [B*W]
-  int32_t* row_live;         // workspace [B*W]
+  int32_t* row_mode;         // workspace [B*W]
+  int32_t* row_nvalid;       // workspace [B*W]
+  float* chunk_key;          // workspace [B*W*kChunksPerRow]
 };
 
 struct MaskView {
@@ -82,131 +100,251 @@ __device__ __forceinline__ void row_children(const SelCtx& c, const MaskView& mv
   }
 }
 
-// ------------------------------------------------------------------------------------------------
-// Kernel 1: per-row statistics.
-// ------------------------------------------------------------------------------------------------
+// Does this row get gathered (true) or streamed (false)?  Same decision in every kernel.
+__device__ __forceinline__ bool row_is_sparse(const SelCtx& c, int n_children) {
+  return c.blob && c.step >= 1 && !(c.flags & GR_SELECT_FORCE_DENSE) && n_children <= kSparseMax;
+}
+
+// Token held by element slot e of chunk k of a dense row (or >= V when the slot is empty).
+__device__ __forceinline__ int dense_slot_token(const SelCtx& c, int k, int e) {
+  return c.vec4 ? 4 * (k + kChunksPerRow * (e >> 2)) + (e & 3) : k + kChunksPerRow * e;
+}
+
+__device__ __forceinline__ int lower_bound_i32(const int32_t* a, int n, int key) {
+  int lo = 0, hi = n;
+  while (lo < hi) { int mid = (lo + hi) >> 1; if (a[mid] < key) lo = mid + 1; else hi = mid; }
+  return lo;
+}
+
+template <int NWAVES>
 __device__ __forceinline__ float block_max(float v, float* s_red) {
   v = gr_wave_max(v);
-  const int wave = threadIdx.x >> 6;
   __syncthreads();
-  if (gr_lane() == 0) s_red[wave] = v;
+  if (gr_lane() == 0) s_red[threadIdx.x >> 6] = v;
   __syncthreads();
   float r = s_red[0];
-  for (int i = 1; i < (int)(blockDim.x >> 6); i++) r = fmaxf(r, s_red[i]);
+#pragma unroll
+  for (int i = 1; i < NWAVES; i++) r = fmaxf(r, s_red[i]);
   return r;
 }
+template <int NWAVES>
 __device__ __forceinline__ double block_sum(double v, double* s_red) {
   v = gr_wave_sum(v);
-  const int wave = threadIdx.x >> 6;
   __syncthreads();
-  if (gr_lane() == 0) s_red[wave] = v;
+  if (gr_lane() == 0) s_red[threadIdx.x >> 6] = v;
   __syncthreads();
   double r = s_red[0];
-  for (int i = 1; i < (int)(blockDim.x >> 6); i++) r += s_red[i];
+#pragma unroll
+  for (int i = 1; i < NWAVES; i++) r += s_red[i];
+  return r;
+}
+template <int NWAVES>
+__device__ __forceinline__ uint32_t block_sum_u32(uint32_t v, uint32_t* s_red) {
+  v = gr_wave_sum_u32(v);
+  __syncthreads();
+  if (gr_lane() == 0) s_red[threadIdx.x >> 6] = v;
+  __syncthreads();
+  uint32_t r = s_red[0];
+#pragma unroll
+  for (int i = 1; i < NWAVES; i++) r += s_red[i];
   return r;
 }
 
-__global__ void __launch_bounds__(kRowThreads) k_row_stats(SelCtx c) {
+// ------------------------------------------------------------------------------------------------
+// Rows that are streamed in full.
+// ------------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(kRowThreads) k_row_dense(SelCtx c, int owns_dead) {
   __shared__ uint32_t s_mask[kMaxMaskWords];
   __shared__ float s_redf[kRowThreads / 64];
   __shared__ double s_redd[kRowThreads / 64];
+  __shared__ uint32_t s_redu[kRowThreads / 64];
+  __shared__ float s_bias;
   const int row = blockIdx.x;
   const int tid = threadIdx.x;
   const float s_in = c.scores_in[row];
   if (!(s_in > -INFINITY)) {
-    if (tid == 0) { c.row_live[row] = 0; c.row_bias[row] = -INFINITY; }
+    if (owns_dead && tid == 0) { c.row_mode[row] = ROW_DEAD; c.row_bias[row] = -INFINITY; c.row_nvalid[row] = 0; }
     return;
   }
-  const float* x = c.logits + (size_t)row * c.V;
   const int V = c.V;
-  const bool force_dense = (c.flags & GR_SELECT_FORCE_DENSE) != 0;
-
   const int32_t* list = nullptr;
   int n_list = 0;
-  bool sparse = false;
   MaskView mv;
   if (c.blob) {
     mv = mask_view(c.blob);
     if (c.step >= 1) {
       row_children(c, mv, row, &list, &n_list);
-      sparse = !force_dense && n_list <= kSparseMax;
+      if (row_is_sparse(c, n_list)) return;      // k_row_sparse owns this row
     }
   }
-
-  float m = -INFINITY;
-  double S = 0.0;
-  if (sparse) {
-    // gather only the valid logits (the sparse mask form of Section 6.1)
-    for (int i = tid; i < n_list; i += kRowThreads) m = fmaxf(m, x[list[i]]);
-    m = block_max(m, s_redf);
-    if (m > -INFINITY)
-      for (int i = tid; i < n_list; i += kRowThreads) S += exp((double)x[list[i]] - (double)m);
+  // ---- validity bits of the row in LDS
+  const int words = (V + 31) >> 5;
+  if (!c.blob) {
+    for (int i = tid; i < words; i += kRowThreads) s_mask[i] = 0xffffffffu;
+  } else if (c.step == 0) {
+    for (int i = tid; i < words; i += kRowThreads) s_mask[i] = mv.l0[i];
+  } else if (c.step == 1) {
+    const int t1 = c.prefix_in[(size_t)row * c.depth];
+    const bool ok = t1 >= 0 && t1 < V;
+    const uint32_t* src = mv.l1 + (size_t)(ok ? t1 : 0) * mv.words;
+    for (int i = tid; i < words; i += kRowThreads) s_mask[i] = ok ? src[i] : 0u;
   } else {
-    // dense: a V-bit validity row in LDS, then stream the logits
-    const int words = (V + 31) >> 5;
-    if (!c.blob) {
-      for (int i = tid; i < words; i += kRowThreads) s_mask[i] = 0xffffffffu;
-    } else if (c.step == 0) {
-      for (int i = tid; i < words; i += kRowThreads) s_mask[i] = mv.l0[i];
-    } else if (c.step == 1) {
-      const int t1 = c.prefix_in[(size_t)row * c.depth];
-      const bool ok = t1 >= 0 && t1 < V;
-      const uint32_t* src = mv.l1 + (size_t)(ok ? t1 : 0) * mv.words;
-      for (int i = tid; i < words; i += kRowThreads) s_mask[i] = ok ? src[i] : 0u;
-    } else {
-      // last level has no dense mask: set the row's few valid positions in an empty mask
-      for (int i = tid; i < words; i += kRowThreads) s_mask[i] = 0u;
-      __syncthreads();
-      for (int i = tid; i < n_list; i += kRowThreads) { const int v = list[i]; atomicOr(&s_mask[v >> 5], 1u << (v & 31)); }
-    }
+    // the last level has no dense mask: set the row's valid positions in an empty one
+    for (int i = tid; i < words; i += kRowThreads) s_mask[i] = 0u;
     __syncthreads();
-    for (int v = tid; v < V; v += kRowThreads)
-      if ((s_mask[v >> 5] >> (v & 31)) & 1u) m = fmaxf(m, x[v]);
-    m = block_max(m, s_redf);
-    if (m > -INFINITY)
-      for (int v = tid; v < V; v += kRowThreads)
-        if ((s_mask[v >> 5] >> (v & 31)) & 1u) S += exp((double)x[v] - (double)m);
+    for (int i = tid; i < n_list; i += kRowThreads) { const int v = list[i]; atomicOr(&s_mask[v >> 5], 1u << (v & 31)); }
+  }
+  __syncthreads();
+
+  const float* x = c.logits + (size_t)row * V;
+  float lmax = -INFINITY;     // this thread's chunk: best valid logit
+  uint32_t nval = 0;
+  double S = 0.0;
+  float m;
+  if (c.vec4 && V <= kRegV4 * 4 * kRowThreads) {
+    // one HBM read: the row stays in registers
+    const int nv4 = V >> 2;
+    float4 xr[kRegV4];
+    uint32_t vb[kRegV4];
+#pragma unroll
+    for (int i = 0; i < kRegV4; i++) {
+      const int p = tid + i * kRowThreads;
+      xr[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+      vb[i] = 0;
+      if (p < nv4) {
+        xr[i] = *(const float4*)(x + 4 * (size_t)p);
+        vb[i] = (s_mask[p >> 3] >> (4 * (p & 7))) & 0xfu;
+        if (4 * p + 3 >= V) vb[i] &= (1u << (V - 4 * p)) - 1u;
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < kRegV4; i++) {
+      if (vb[i] & 1u) lmax = fmaxf(lmax, xr[i].x);
+      if (vb[i] & 2u) lmax = fmaxf(lmax, xr[i].y);
+      if (vb[i] & 4u) lmax = fmaxf(lmax, xr[i].z);
+      if (vb[i] & 8u) lmax = fmaxf(lmax, xr[i].w);
+      nval += __popc(vb[i]);
+    }
+    m = block_max<kRowThreads / 64>(lmax, s_redf);
+    if (m > -INFINITY) {
+      const double md = (double)m;
+#pragma unroll
+      for (int i = 0; i < kRegV4; i++) {
+        if (vb[i] & 1u) S += exp((double)xr[i].x - md);
+        if (vb[i] & 2u) S += exp((double)xr[i].y - md);
+        if (vb[i] & 4u) S += exp((double)xr[i].z - md);
+        if (vb[i] & 8u) S += exp((double)xr[i].w - md);
+      }
+    }
+  } else {
+    // general shape: two passes over the row (the second one hits in cache); same chunk layout
+    const int epc = c.epc;
+    for (int e = 0; e < epc; e++) {
+      const int v = dense_slot_token(c, tid, e);
+      if (v < V && ((s_mask[v >> 5] >> (v & 31)) & 1u)) { lmax = fmaxf(lmax, x[v]); nval++; }
+    }
+    m = block_max<kRowThreads / 64>(lmax, s_redf);
+    if (m > -INFINITY) {
+      const double md = (double)m;
+      for (int e = 0; e < epc; e++) {
+        const int v = dense_slot_token(c, tid, e);
+        if (v < V && ((s_mask[v >> 5] >> (v & 31)) & 1u)) S += exp((double)x[v] - md);
+      }
+    }
   }
   if (!(m > -INFINITY)) {
-    if (tid == 0) { c.row_live[row] = 0; c.row_bias[row] = -INFINITY; }
+    if (tid == 0) { c.row_mode[row] = ROW_DEAD; c.row_bias[row] = -INFINITY; c.row_nvalid[row] = 0; }
     return;
   }
-  S = block_sum(S, s_redd);
+  S = block_sum<kRowThreads / 64>(S, s_redd);
+  nval = block_sum_u32<kRowThreads / 64>(nval, s_redu);
   if (tid == 0) {
     const float lse = (float)((double)m + log(S));
-    c.row_bias[row] = __fsub_rn(s_in, lse);
-    c.row_live[row] = 1;
+    const float bias = __fsub_rn(s_in, lse);
+    s_bias = bias;
+    c.row_bias[row] = bias;
+    c.row_mode[row] = ROW_DENSE;
+    c.row_nvalid[row] = (int32_t)nval;
   }
+  __syncthreads();
+  c.chunk_key[(size_t)row * kChunksPerRow + tid] = (lmax > -INFINITY) ? __fadd_rn(s_bias, lmax) : -INFINITY;
 }
 
 // ------------------------------------------------------------------------------------------------
-// Kernel 2: exact top-W per request.
+// Rows with few valid children: one wavefront each, gather only the valid logits (Section 6.1's
+// sparse form).  Chunk k of such a row = children k, k+64, k+128, ...
 // ------------------------------------------------------------------------------------------------
-// Visit every finite candidate of request b: f(score, flat, pred) is called wave-convergently
-// (pred = this lane holds a candidate).
+__global__ void __launch_bounds__(kRowThreads) k_row_sparse(SelCtx c) {
+  const int row = blockIdx.x * (kRowThreads / 64) + (threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
+  if (row >= c.B * c.W) return;
+  const float s_in = c.scores_in[row];
+  if (!(s_in > -INFINITY)) {
+    if (lane == 0) { c.row_mode[row] = ROW_DEAD; c.row_bias[row] = -INFINITY; c.row_nvalid[row] = 0; }
+    return;
+  }
+  const MaskView mv = mask_view(c.blob);
+  const int32_t* list;
+  int n;
+  row_children(c, mv, row, &list, &n);
+  if (!row_is_sparse(c, n)) return;            // k_row_dense owns this row
+  if (n == 0) {
+    if (lane == 0) { c.row_mode[row] = ROW_DEAD; c.row_bias[row] = -INFINITY; c.row_nvalid[row] = 0; }
+    return;
+  }
+  const float* x = c.logits + (size_t)row * c.V;
+  float xv[kSparseMax / 64];
+  float lmax = -INFINITY;
+#pragma unroll
+  for (int k = 0; k < kSparseMax / 64; k++) {
+    const int i = lane + 64 * k;
+    xv[k] = (i < n) ? x[list[i]] : -INFINITY;
+    lmax = fmaxf(lmax, xv[k]);
+  }
+  const float m = gr_wave_max(lmax);
+  double S = 0.0;
+  const double md = (double)m;
+#pragma unroll
+  for (int k = 0; k < kSparseMax / 64; k++)
+    if (lane + 64 * k < n) S += exp((double)xv[k] - md);
+  S = gr_wave_sum(S);
+  const float lse = (float)((double)m + log(S));
+  const float bias = __fsub_rn(s_in, lse);
+  if (lane == 0) { c.row_bias[row] = bias; c.row_mode[row] = ROW_SPARSE; c.row_nvalid[row] = n; }
+  c.chunk_key[(size_t)row * kChunksPerRow + lane] = (lmax > -INFINITY) ? __fadd_rn(bias, lmax) : -INFINITY;
+}
+
+// ------------------------------------------------------------------------------------------------
+// Per-request selection.
+// ------------------------------------------------------------------------------------------------
+// Visit every finite candidate of request b.  f(score, flat, pred) is called wave-convergently
+// (pred = this lane holds a candidate).  Rows given by bit masks are strided by the whole
+// workgroup; rows given by child lists are taken one per wavefront.
 template <class F>
 __device__ __forceinline__ void for_each_candidate(const SelCtx& c, const MaskView& mv, int b, F&& f) {
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, nw = blockDim.x >> 6;
-  for (int w = wave; w < c.W; w += nw) {
-    const int row = b * c.W + w;
-    if (!c.row_live[row]) continue;
-    const float bias = c.row_bias[row];
-    const float* x = c.logits + (size_t)row * c.V;
-    const uint32_t flat0 = (uint32_t)w * (uint32_t)c.V;
-    if (!c.blob) {
-      for (int v0 = 0; v0 < c.V; v0 += 64) {
-        const int v = v0 + lane;
-        const bool pred = v < c.V;
+  if (!c.blob || c.step == 0) {
+    for (int w = 0; w < c.W; w++) {
+      const int row = b * c.W + w;
+      if (c.row_mode[row] == ROW_DEAD) continue;
+      const float bias = c.row_bias[row];
+      const float* x = c.logits + (size_t)row * c.V;
+      const uint32_t flat0 = (uint32_t)w * (uint32_t)c.V;
+      for (int v0 = 0; v0 < c.V; v0 += blockDim.x) {
+        const int v = v0 + threadIdx.x;
+        const bool pred = v < c.V && (!c.blob || ((mv.l0[v >> 5] >> (v & 31)) & 1u));
         f(pred ? __fadd_rn(bias, x[v]) : 0.f, flat0 + v, pred);
       }
-    } else if (c.step == 0) {
-      for (int v0 = 0; v0 < c.V; v0 += 64) {
-        const int v = v0 + lane;
-        const bool pred = v < c.V && ((mv.l0[v >> 5] >> (v & 31)) & 1u);
-        f(pred ? __fadd_rn(bias, x[v]) : 0.f, flat0 + v, pred);
-      }
-    } else {
-      const int32_t* list; int n;
+    }
+  } else {
+    for (int w = wave; w < c.W; w += nw) {
+      const int row = b * c.W + w;
+      if (c.row_mode[row] == ROW_DEAD) continue;
+      const float bias = c.row_bias[row];
+      const float* x = c.logits + (size_t)row * c.V;
+      const uint32_t flat0 = (uint32_t)w * (uint32_t)c.V;
+      const int32_t* list;
+      int n;
       row_children(c, mv, row, &list, &n);
       for (int i0 = 0; i0 < n; i0 += 64) {
         const int i = i0 + lane;
@@ -222,22 +360,18 @@ __device__ __forceinline__ uint64_t composite(float score, uint32_t flat) {
   return ((uint64_t)gr_ordkey(score) << 32) | (uint64_t)(0xffffffffu - flat);
 }
 
-__device__ __forceinline__ int lower_bound_i32(const int32_t* a, int n, int key) {
-  int lo = 0, hi = n;
-  while (lo < hi) { int mid = (lo + hi) >> 1; if (a[mid] < key) lo = mid + 1; else hi = mid; }
-  return lo;
+// Monotone (non-increasing in the score) bin index below the request's best chunk key.
+__device__ __forceinline__ int key_bin(float hi, float score) {
+  return (int)fminf((hi - score) * 64.0f, (float)(kHistBins - 1));
 }
 
-__global__ void __launch_bounds__(kSelThreads) k_select(SelCtx c) {
-  __shared__ uint32_t s_hist[2048];
-  __shared__ uint64_t s_list[kListCap];
+// Exact MSB radix select of the W best composite keys over ALL candidates (slow, always correct).
+// Leaves the survivors in s_list and returns their number.
+__device__ int radix_select_all(const SelCtx& c, const MaskView& mv, int b, uint64_t* s_list, uint32_t* s_hist) {
   __shared__ uint64_t s_prefix;
   __shared__ uint32_t s_need, s_bin, s_cnt;
   __shared__ int s_all;
-  const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63;
-  MaskView mv;
-  if (c.blob) mv = mask_view(c.blob);
-
+  const int tid = threadIdx.x, lane = tid & 63;
   uint64_t prefix = 0;       // digits chosen so far (the top 64-shift bits of the W-th largest key)
   uint32_t need = (uint32_t)c.W;
   int shift = 64;            // number of key bits not yet fixed
@@ -299,7 +433,6 @@ __global__ void __launch_bounds__(kSelThreads) k_select(SelCtx c) {
     // everything above the bin (W - need keys) plus the bin itself fits in LDS: stop refining
     if ((uint32_t)c.W - need + s_bin <= (uint32_t)kListCap) break;
   }
-
   if (tid == 0) s_cnt = 0;
   __syncthreads();
   for_each_candidate(c, mv, b, [&](float score, uint32_t flat, bool pred) {
@@ -310,7 +443,142 @@ __global__ void __launch_bounds__(kSelThreads) k_select(SelCtx c) {
     }
   });
   __syncthreads();
-  const int n = min((int)s_cnt, kListCap);
+  return min((int)s_cnt, kListCap);
+}
+
+__global__ void __launch_bounds__(kSelThreads) k_select(SelCtx c) {
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  uint64_t* s_list = (uint64_t*)smem;
+  uint32_t* s_hist = (uint32_t*)(smem + (size_t)kListCap * 8);
+  uint32_t* s_chunks = (uint32_t*)(smem + (size_t)kListCap * 8 + (size_t)kHistBins * 4);
+  __shared__ float s_redf[kSelThreads / 64];
+  __shared__ uint32_t s_redu[kSelThreads / 64];
+  __shared__ uint32_t s_n, s_nc;
+  __shared__ int s_thr;
+  const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  constexpr int NW = kSelThreads / 64;
+  MaskView mv;
+  if (c.blob) mv = mask_view(c.blob);
+
+  // ---- how many candidates does this request have?
+  uint32_t cnt = 0;
+  for (int w = tid; w < c.W; w += kSelThreads) cnt += (uint32_t)c.row_nvalid[b * c.W + w];
+  const uint32_t total = block_sum_u32<NW>(cnt, s_redu);
+  if (tid == 0) { s_n = 0; s_nc = 0; }
+  __syncthreads();
+
+  int n = 0;
+  bool need_fallback = false;
+  if (total <= (uint32_t)kListCap) {
+    // few candidates (first level from a single root, last level): take them all
+    for_each_candidate(c, mv, b, [&](float score, uint32_t flat, bool pred) {
+      if (pred) { const uint32_t idx = atomicAdd(&s_n, 1u); if (idx < (uint32_t)kListCap) s_list[idx] = composite(score, flat); }
+    });
+    __syncthreads();
+    n = min((int)s_n, kListCap);
+  } else {
+    // ---- threshold from the chunk keys: the best candidate of every chunk
+    auto for_each_chunk_key = [&](auto&& f) {
+      for (int w = wave; w < c.W; w += NW) {
+        const int row = b * c.W + w;
+        const int mode = c.row_mode[row];
+        if (mode == ROW_DEAD) continue;
+        const int nk = (mode == ROW_DENSE) ? kChunksPerRow : 64;
+        for (int k = lane; k < nk; k += 64) f(c.chunk_key[(size_t)row * kChunksPerRow + k], w, k);
+      }
+    };
+    float hi = -INFINITY;
+    for_each_chunk_key([&](float key, int, int) { hi = fmaxf(hi, key); });
+    hi = block_max<NW>(hi, s_redf);
+    for (int i = tid; i < kHistBins; i += kSelThreads) s_hist[i] = 0;
+    __syncthreads();
+    for_each_chunk_key([&](float key, int, int) { if (key > -INFINITY) atomicAdd(&s_hist[key_bin(hi, key)], 1u); });
+    __syncthreads();
+    if (tid < 64) {
+      // smallest bin t with at least W chunk keys in bins 0..t (bin 0 = best scores)
+      constexpr int per = kHistBins / 64;
+      uint32_t local = 0;
+      for (int i = 0; i < per; i++) local += s_hist[lane * per + i];
+      uint32_t incl = local;   // inclusive prefix sum over lanes
+      for (int o = 1; o < 64; o <<= 1) {
+        uint32_t v = __shfl_up(incl, o, 64);
+        if (lane >= o) incl += v;
+      }
+      const uint32_t tot = __shfl(incl, 63, 64);
+      const uint32_t below = incl - local;
+      if (tot < (uint32_t)c.W) {
+        if (lane == 0) s_thr = kHistBins - 1;      // fewer chunks than slots: no threshold
+      } else if (below < (uint32_t)c.W && (uint32_t)c.W <= incl) {
+        uint32_t acc = below;
+        int bin = lane * per;
+        for (;; bin++) { acc += s_hist[bin]; if (acc >= (uint32_t)c.W) break; }
+        s_thr = bin;
+      }
+    }
+    __syncthreads();
+    const int thr = s_thr;
+    // ---- chunks that reach the threshold
+    for_each_chunk_key([&](float key, int w, int k) {
+      if (key > -INFINITY && key_bin(hi, key) <= thr) {
+        const uint32_t idx = atomicAdd(&s_nc, 1u);
+        if (idx < (uint32_t)kChunkCap) s_chunks[idx] = ((uint32_t)w << 8) | (uint32_t)k;
+      }
+    });
+    __syncthreads();
+    const int nc = (int)s_nc;
+    if (nc > kChunkCap) {
+      need_fallback = true;
+    } else {
+      // ---- re-read only those chunks; keep their candidates that reach the threshold
+      const int epc = max(c.epc, kSparseMax / 64);
+      for (int idx = tid; idx < nc * epc; idx += kSelThreads) {
+        const uint32_t ent = s_chunks[idx / epc];
+        const int e = idx % epc;
+        const int w = (int)(ent >> 8), k = (int)(ent & 255u);
+        const int row = b * c.W + w;
+        int v = -1;
+        if (c.row_mode[row] == ROW_DENSE) {
+          if (e < c.epc) {
+            const int t = dense_slot_token(c, k, e);
+            if (t < c.V) {
+              bool ok = true;
+              if (c.blob) {
+                if (c.step == 0) ok = (mv.l0[t >> 5] >> (t & 31)) & 1u;
+                else if (c.step == 1) {
+                  const int t1 = c.prefix_in[(size_t)row * c.depth];
+                  ok = (mv.l1[(size_t)t1 * mv.words + (t >> 5)] >> (t & 31)) & 1u;
+                } else {
+                  const int32_t* list; int nl;
+                  row_children(c, mv, row, &list, &nl);
+                  const int pos = lower_bound_i32(list, nl, t);
+                  ok = pos < nl && list[pos] == t;
+                }
+              }
+              if (ok) v = t;
+            }
+          }
+        } else {
+          const int32_t* list; int nl;
+          row_children(c, mv, row, &list, &nl);
+          const int i = k + 64 * e;
+          if (e < kSparseMax / 64 && i < nl) v = list[i];
+        }
+        if (v >= 0) {
+          const float score = __fadd_rn(c.row_bias[row], c.logits[(size_t)row * c.V + v]);
+          if (key_bin(hi, score) <= thr) {
+            const uint32_t pos = atomicAdd(&s_n, 1u);
+            if (pos < (uint32_t)kListCap) s_list[pos] = composite(score, (uint32_t)w * (uint32_t)c.V + (uint32_t)v);
+          }
+        }
+      }
+      __syncthreads();
+      if (s_n > (uint32_t)kListCap) need_fallback = true;
+      n = min((int)s_n, kListCap);
+    }
+    if (need_fallback) n = radix_select_all(c, mv, b, s_list, s_hist);
+  }
+
+  // ---- order the survivors (descending composite key = score descending, flat index ascending)
   int n2 = 1;
   while (n2 < n) n2 <<= 1;
   for (int i = n + tid; i < n2; i += kSelThreads) s_list[i] = 0;   // 0 sorts after every real key
@@ -329,7 +597,7 @@ __global__ void __launch_bounds__(kSelThreads) k_select(SelCtx c) {
     }
   }
 
-  // write the new beam state, best first
+  // ---- write the new beam state, best first
   for (int j = tid; j < c.W; j += kSelThreads) {
     const size_t o = (size_t)b * c.W + j;
     int32_t* po = c.prefix_out + o * c.depth;
@@ -376,7 +644,8 @@ __global__ void __launch_bounds__(kSelThreads) k_select(SelCtx c) {
 
 extern "C" size_t gr_beam_select_workspace_bytes(int32_t B, int32_t W, int32_t V, int32_t depth) {
   if (B <= 0 || W <= 0 || V <= 0 || depth <= 0) return 0;
-  return 2 * gr_align256((size_t)B * W * 4);
+  const size_t rows = (size_t)B * W;
+  return 3 * gr_align256(rows * 4) + gr_align256(rows * kChunksPerRow * 4);
 }
 
 extern "C" gr_status gr_beam_select(const gr_select_params* p, void* workspace, size_t workspace_bytes, void* stream_) {
@@ -395,15 +664,26 @@ extern "C" gr_status gr_beam_select(const gr_select_params* p, void* workspace, 
 
   SelCtx c;
   c.B = p->B; c.W = p->W; c.V = p->V; c.depth = p->depth; c.step = p->step; c.flags = p->flags;
+  c.vec4 = (p->V % 4 == 0) && (((uintptr_t)p->logits & 15) == 0);
+  c.epc = c.vec4 ? 4 * ((p->V / 4 + kChunksPerRow - 1) / kChunksPerRow) : (p->V + kChunksPerRow - 1) / kChunksPerRow;
   c.blob = (const char*)p->mask;
   c.logits = p->logits; c.scores_in = p->scores_in; c.prefix_in = p->prefix_in; c.range_in = p->range_in;
   c.parent_out = p->parent_out; c.token_out = p->token_out; c.scores_out = p->scores_out;
   c.prefix_out = p->prefix_out; c.range_out = p->range_out; c.item_index_out = p->item_index_out;
-  c.row_bias = (float*)workspace;
-  c.row_live = (int32_t*)((char*)workspace + gr_align256((size_t)p->B * p->W * 4));
+  const size_t rows = (size_t)p->B * p->W;
+  char* ws = (char*)workspace;
+  c.row_bias = (float*)ws;                 ws += gr_align256(rows * 4);
+  c.row_mode = (int32_t*)ws;               ws += gr_align256(rows * 4);
+  c.row_nvalid = (int32_t*)ws;             ws += gr_align256(rows * 4);
+  c.chunk_key = (float*)ws;
 
-  hipLaunchKernelGGL(k_row_stats, dim3(p->B * p->W), dim3(kRowThreads), 0, stream, c);
-  hipLaunchKernelGGL(k_select, dim3(p->B), dim3(kSelThreads), 0, stream, c);
+  const bool has_sparse = p->mask && p->step >= 1 && !(p->flags & GR_SELECT_FORCE_DENSE);
+  if (has_sparse)
+    hipLaunchKernelGGL(k_row_sparse, dim3((unsigned)((rows + 3) / 4)), dim3(kRowThreads), 0, stream, c);
+  hipLaunchKernelGGL(k_row_dense, dim3((unsigned)rows), dim3(kRowThreads), 0, stream, c, has_sparse ? 0 : 1);
+  // more than 64 KB of LDS must be opted into (per device; cheap, so done on every call)
+  GR_HIP_TRY(hipFuncSetAttribute((const void*)k_select, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kSelLdsBytes));
+  hipLaunchKernelGGL(k_select, dim3(p->B), dim3(kSelThreads), kSelLdsBytes, stream, c);
   GR_HIP_TRY(hipGetLastError());
   return GR_OK;
 }

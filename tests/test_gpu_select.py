@@ -110,7 +110,7 @@ def test_random_shapes_masked(gr, oracle_lib, B, W, V, n, flags):
     _three_steps(gr, oracle_lib, items, lambda s: (2.5 * rng.standard_normal((B, W, V))).astype(np.float32), B, W, V, flags)
 
 
-@pytest.mark.parametrize("B,W,V", [(2, 16, 256), (1, 100, 999), (3, 64, 8192), (1, 1, 5)])
+@pytest.mark.parametrize("B,W,V", [(2, 16, 256), (1, 100, 999), (3, 64, 8192), (1, 1, 5), (2, 9, 20000), (1, 300, 4096)])
 def test_unconstrained_all_beams_live(gr, oracle_lib, B, W, V):
     rng = np.random.default_rng(V)
     logits = (2.0 * rng.standard_normal((B, W, V))).astype(np.float32)
@@ -137,6 +137,19 @@ def test_ties_resolved_by_lowest_flat_index(gr, oracle_lib):
     got = run_select(gr, None, logits, sc, pf, rg, 0)
     assert_select_equal(got, oracle_lib.beam_select(None, logits, sc, pf, 0))
     np.testing.assert_array_equal(got["parent"][0], np.zeros(W)); np.testing.assert_array_equal(got["token"][0], np.arange(W))
+
+
+@pytest.mark.parametrize("W,V,levels", [(64, 1024, 1), (40, 8192, 3), (256, 2048, 7)])
+def test_massive_ties_take_the_exact_fallback(gr, oracle_lib, W, V, levels):
+    # tens of thousands of exactly equal candidates: the survivors cannot fit in LDS, so the exact
+    # radix select over all candidates must produce the same beams
+    rng = np.random.default_rng(W + V)
+    logits = rng.integers(0, levels, size=(2, W, V)).astype(np.float32)
+    sc = np.zeros((2, W), np.float32)
+    sc[1] = -np.round(rng.random(W) * 2)
+    pf = np.full((2, W, 3), -1, np.int32)
+    rg = np.zeros((2, W, 2), np.int32)
+    assert_select_equal(run_select(gr, None, logits, sc, pf, rg, 0), oracle_lib.beam_select(None, logits, sc, pf, 0))
 
 
 def test_dead_beams_and_fewer_candidates_than_slots(gr, oracle_lib):
