@@ -163,7 +163,10 @@ __global__ void __launch_bounds__(kRowThreads) k_row_dense(SelCtx c, int owns_de
   const int tid = threadIdx.x;
   const float s_in = c.scores_in[row];
   if (!(s_in > -INFINITY)) {
-    if (owns_dead && tid == 0) { c.row_mode[row] = ROW_DEAD; c.row_bias[row] = -INFINITY; c.row_nvalid[row] = 0; }
+    if (owns_dead) {
+      if (tid == 0) { c.row_mode[row] = ROW_DEAD; c.row_bias[row] = -INFINITY; c.row_nvalid[row] = 0; }
+      c.chunk_key[(size_t)row * kChunksPerRow + tid] = -INFINITY;
+    }
     return;
   }
   const int V = c.V;
@@ -254,6 +257,7 @@ __global__ void __launch_bounds__(kRowThreads) k_row_dense(SelCtx c, int owns_de
   }
   if (!(m > -INFINITY)) {
     if (tid == 0) { c.row_mode[row] = ROW_DEAD; c.row_bias[row] = -INFINITY; c.row_nvalid[row] = 0; }
+    c.chunk_key[(size_t)row * kChunksPerRow + tid] = -INFINITY;
     return;
   }
   S = block_sum<kRowThreads / 64>(S, s_redd);
@@ -278,18 +282,22 @@ __global__ void __launch_bounds__(kRowThreads) k_row_sparse(SelCtx c) {
   const int row = blockIdx.x * (kRowThreads / 64) + (threadIdx.x >> 6);
   const int lane = threadIdx.x & 63;
   if (row >= c.B * c.W) return;
+  float* keys = c.chunk_key + (size_t)row * kChunksPerRow;
   const float s_in = c.scores_in[row];
-  if (!(s_in > -INFINITY)) {
-    if (lane == 0) { c.row_mode[row] = ROW_DEAD; c.row_bias[row] = -INFINITY; c.row_nvalid[row] = 0; }
-    return;
-  }
   const MaskView mv = mask_view(c.blob);
-  const int32_t* list;
-  int n;
-  row_children(c, mv, row, &list, &n);
-  if (!row_is_sparse(c, n)) return;            // k_row_dense owns this row
-  if (n == 0) {
+  const int32_t* list = nullptr;
+  int n = 0;
+  const bool live = s_in > -INFINITY;
+  if (live) {
+    row_children(c, mv, row, &list, &n);
+    if (!row_is_sparse(c, n)) return;          // k_row_dense owns this row
+  }
+  // every key slot of the row is defined: unused ones hold -inf
+#pragma unroll
+  for (int k = 1; k < kChunksPerRow / 64; k++) keys[lane + 64 * k] = -INFINITY;
+  if (!live || n == 0) {
     if (lane == 0) { c.row_mode[row] = ROW_DEAD; c.row_bias[row] = -INFINITY; c.row_nvalid[row] = 0; }
+    keys[lane] = -INFINITY;
     return;
   }
   const float* x = c.logits + (size_t)row * c.V;
@@ -311,7 +319,7 @@ __global__ void __launch_bounds__(kRowThreads) k_row_sparse(SelCtx c) {
   const float lse = (float)((double)m + log(S));
   const float bias = __fsub_rn(s_in, lse);
   if (lane == 0) { c.row_bias[row] = bias; c.row_mode[row] = ROW_SPARSE; c.row_nvalid[row] = n; }
-  c.chunk_key[(size_t)row * kChunksPerRow + lane] = (lmax > -INFINITY) ? __fadd_rn(bias, lmax) : -INFINITY;
+  keys[lane] = (lmax > -INFINITY) ? __fadd_rn(bias, lmax) : -INFINITY;
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -446,84 +454,80 @@ __device__ int radix_select_all(const SelCtx& c, const MaskView& mv, int b, uint
   return min((int)s_cnt, kListCap);
 }
 
+// Wave 0 only: smallest bin t with at least `want` entries in bins 0..t (bin 0 = best scores); the
+// last bin when there are fewer than `want` entries in total.
+__device__ __forceinline__ void hist_threshold(const uint32_t* s_hist, uint32_t want, int* s_thr) {
+  const int lane = threadIdx.x & 63;
+  constexpr int per = kHistBins / 64;
+  uint32_t local = 0;
+  for (int i = 0; i < per; i++) local += s_hist[lane * per + i];
+  uint32_t incl = local;   // inclusive prefix sum over lanes
+  for (int o = 1; o < 64; o <<= 1) {
+    uint32_t v = __shfl_up(incl, o, 64);
+    if (lane >= o) incl += v;
+  }
+  const uint32_t tot = __shfl(incl, 63, 64);
+  const uint32_t below = incl - local;
+  if (tot < want) {
+    if (lane == 0) *s_thr = kHistBins - 1;
+  } else if (below < want && want <= incl) {
+    uint32_t acc = below;
+    int bin = lane * per;
+    for (;; bin++) { acc += s_hist[bin]; if (acc >= want) break; }
+    *s_thr = bin;
+  }
+}
+
 __global__ void __launch_bounds__(kSelThreads) k_select(SelCtx c) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   uint64_t* s_list = (uint64_t*)smem;
   uint32_t* s_hist = (uint32_t*)(smem + (size_t)kListCap * 8);
   uint32_t* s_chunks = (uint32_t*)(smem + (size_t)kListCap * 8 + (size_t)kHistBins * 4);
   __shared__ float s_redf[kSelThreads / 64];
-  __shared__ uint32_t s_redu[kSelThreads / 64];
   __shared__ uint32_t s_n, s_nc;
   __shared__ int s_thr;
-  const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int b = blockIdx.x, tid = threadIdx.x;
   constexpr int NW = kSelThreads / 64;
   MaskView mv;
   if (c.blob) mv = mask_view(c.blob);
 
-  // ---- how many candidates does this request have?
-  uint32_t cnt = 0;
-  for (int w = tid; w < c.W; w += kSelThreads) cnt += (uint32_t)c.row_nvalid[b * c.W + w];
-  const uint32_t total = block_sum_u32<NW>(cnt, s_redu);
   if (tid == 0) { s_n = 0; s_nc = 0; }
+  // ---- threshold from the chunk keys (the best candidate score of every 1/256th of a row)
+  const float4* keys4 = (const float4*)(c.chunk_key + (size_t)b * c.W * kChunksPerRow);
+  const int nk4 = c.W * kChunksPerRow / 4;
+  float hi = -INFINITY;
+  for (int i = tid; i < nk4; i += kSelThreads) {
+    const float4 k = keys4[i];
+    hi = fmaxf(fmaxf(hi, fmaxf(k.x, k.y)), fmaxf(k.z, k.w));
+  }
+  hi = block_max<NW>(hi, s_redf);
+  for (int i = tid; i < kHistBins; i += kSelThreads) s_hist[i] = 0;
   __syncthreads();
-
   int n = 0;
   bool need_fallback = false;
-  if (total <= (uint32_t)kListCap) {
-    // few candidates (first level from a single root, last level): take them all
-    for_each_candidate(c, mv, b, [&](float score, uint32_t flat, bool pred) {
-      if (pred) { const uint32_t idx = atomicAdd(&s_n, 1u); if (idx < (uint32_t)kListCap) s_list[idx] = composite(score, flat); }
-    });
-    __syncthreads();
-    n = min((int)s_n, kListCap);
-  } else {
-    // ---- threshold from the chunk keys: the best candidate of every chunk
-    auto for_each_chunk_key = [&](auto&& f) {
-      for (int w = wave; w < c.W; w += NW) {
-        const int row = b * c.W + w;
-        const int mode = c.row_mode[row];
-        if (mode == ROW_DEAD) continue;
-        const int nk = (mode == ROW_DENSE) ? kChunksPerRow : 64;
-        for (int k = lane; k < nk; k += 64) f(c.chunk_key[(size_t)row * kChunksPerRow + k], w, k);
-      }
-    };
-    float hi = -INFINITY;
-    for_each_chunk_key([&](float key, int, int) { hi = fmaxf(hi, key); });
-    hi = block_max<NW>(hi, s_redf);
-    for (int i = tid; i < kHistBins; i += kSelThreads) s_hist[i] = 0;
-    __syncthreads();
-    for_each_chunk_key([&](float key, int, int) { if (key > -INFINITY) atomicAdd(&s_hist[key_bin(hi, key)], 1u); });
-    __syncthreads();
-    if (tid < 64) {
-      // smallest bin t with at least W chunk keys in bins 0..t (bin 0 = best scores)
-      constexpr int per = kHistBins / 64;
-      uint32_t local = 0;
-      for (int i = 0; i < per; i++) local += s_hist[lane * per + i];
-      uint32_t incl = local;   // inclusive prefix sum over lanes
-      for (int o = 1; o < 64; o <<= 1) {
-        uint32_t v = __shfl_up(incl, o, 64);
-        if (lane >= o) incl += v;
-      }
-      const uint32_t tot = __shfl(incl, 63, 64);
-      const uint32_t below = incl - local;
-      if (tot < (uint32_t)c.W) {
-        if (lane == 0) s_thr = kHistBins - 1;      // fewer chunks than slots: no threshold
-      } else if (below < (uint32_t)c.W && (uint32_t)c.W <= incl) {
-        uint32_t acc = below;
-        int bin = lane * per;
-        for (;; bin++) { acc += s_hist[bin]; if (acc >= (uint32_t)c.W) break; }
-        s_thr = bin;
-      }
+  if (hi > -INFINITY) {
+    for (int i = tid; i < nk4; i += kSelThreads) {
+      const float4 k = keys4[i];
+      if (k.x > -INFINITY) atomicAdd(&s_hist[key_bin(hi, k.x)], 1u);
+      if (k.y > -INFINITY) atomicAdd(&s_hist[key_bin(hi, k.y)], 1u);
+      if (k.z > -INFINITY) atomicAdd(&s_hist[key_bin(hi, k.z)], 1u);
+      if (k.w > -INFINITY) atomicAdd(&s_hist[key_bin(hi, k.w)], 1u);
     }
+    __syncthreads();
+    if (tid < 64) hist_threshold(s_hist, (uint32_t)c.W, &s_thr);
     __syncthreads();
     const int thr = s_thr;
     // ---- chunks that reach the threshold
-    for_each_chunk_key([&](float key, int w, int k) {
-      if (key > -INFINITY && key_bin(hi, key) <= thr) {
-        const uint32_t idx = atomicAdd(&s_nc, 1u);
-        if (idx < (uint32_t)kChunkCap) s_chunks[idx] = ((uint32_t)w << 8) | (uint32_t)k;
-      }
-    });
+    for (int i = tid; i < nk4; i += kSelThreads) {
+      const float4 k = keys4[i];
+      const float kk[4] = {k.x, k.y, k.z, k.w};
+#pragma unroll
+      for (int j = 0; j < 4; j++)
+        if (kk[j] > -INFINITY && key_bin(hi, kk[j]) <= thr) {
+          const uint32_t idx = atomicAdd(&s_nc, 1u);
+          if (idx < (uint32_t)kChunkCap) s_chunks[idx] = (uint32_t)(4 * i + j);     // = w * 256 + chunk
+        }
+    }
     __syncthreads();
     const int nc = (int)s_nc;
     if (nc > kChunkCap) {
@@ -576,6 +580,35 @@ __global__ void __launch_bounds__(kSelThreads) k_select(SelCtx c) {
       n = min((int)s_n, kListCap);
     }
     if (need_fallback) n = radix_select_all(c, mv, b, s_list, s_hist);
+
+    // ---- many survivors (few chunks, or a coarse first threshold): refine on the scores themselves
+    if (n > 2 * c.W) {
+      uint64_t mine[kListCap / kSelThreads];
+      float top = -INFINITY;
+#pragma unroll
+      for (int k = 0; k < kListCap / kSelThreads; k++) {
+        const int i = tid + k * kSelThreads;
+        mine[k] = (i < n) ? s_list[i] : 0;
+        if (i < n) top = fmaxf(top, gr_ordkey_inv((uint32_t)(mine[k] >> 32)));
+      }
+      top = block_max<NW>(top, s_redf);
+      for (int i = tid; i < kHistBins; i += kSelThreads) s_hist[i] = 0;
+      if (tid == 0) s_n = 0;
+      __syncthreads();
+#pragma unroll
+      for (int k = 0; k < kListCap / kSelThreads; k++)
+        if (tid + k * kSelThreads < n) atomicAdd(&s_hist[key_bin(top, gr_ordkey_inv((uint32_t)(mine[k] >> 32)))], 1u);
+      __syncthreads();
+      if (tid < 64) hist_threshold(s_hist, (uint32_t)c.W, &s_thr);
+      __syncthreads();
+      const int thr2 = s_thr;
+#pragma unroll
+      for (int k = 0; k < kListCap / kSelThreads; k++)
+        if (tid + k * kSelThreads < n && key_bin(top, gr_ordkey_inv((uint32_t)(mine[k] >> 32))) <= thr2)
+          s_list[atomicAdd(&s_n, 1u)] = mine[k];
+      __syncthreads();
+      n = (int)s_n;
+    }
   }
 
   // ---- order the survivors (descending composite key = score descending, flat index ascending)
