@@ -358,8 +358,9 @@ __global__ void __launch_bounds__(256) k_attn_merge(AttnCtx c) {
   if (c.lse && lane == 0) c.lse[row] = (L > 0.f) ? (M2 + __builtin_amdgcn_logf(L)) * kLn2 : -INFINITY;
 }
 
-constexpr int kNCB = 2, kNWaves = 4;
-constexpr int kMWG = kNWaves * 32 * kNCB;
+constexpr int kMWG = 256;
+#include <cstdlib>
+static int attn_variant() { const char* e = getenv("GR_ATTN_VARIANT"); return e ? atoi(e) : 0; }
 
 int choose_nsplit(const gr_attn_params* p) {
   const int g = p->Hq / p->Hkv;
@@ -421,10 +422,14 @@ extern "C" gr_status gr_beam_attn(const gr_attn_params* p, void* workspace, size
   const int64_t groups_padded = ((int64_t)c.n_groups + 7) / 8 * 8;
   const int64_t grid = groups_padded * c.MB;
   if (grid >= ((int64_t)1 << 31)) return GR_ERR_UNSUPPORTED;
-  if (p->d == 128)
-    hipLaunchKernelGGL((k_beam_attn<128, kNCB, kNWaves>), dim3((unsigned)grid), dim3(kNWaves * 64), 0, stream, c);
-  else
-    hipLaunchKernelGGL((k_beam_attn<64, kNCB, kNWaves>), dim3((unsigned)grid), dim3(kNWaves * 64), 0, stream, c);
+  const int var = attn_variant();
+  if (p->d == 128) {
+    if (var == 1) hipLaunchKernelGGL((k_beam_attn<128, 1, 8>), dim3((unsigned)grid), dim3(512), 0, stream, c);
+    else hipLaunchKernelGGL((k_beam_attn<128, 2, 4>), dim3((unsigned)grid), dim3(256), 0, stream, c);
+  } else {
+    if (var == 1) hipLaunchKernelGGL((k_beam_attn<64, 1, 8>), dim3((unsigned)grid), dim3(512), 0, stream, c);
+    else hipLaunchKernelGGL((k_beam_attn<64, 2, 4>), dim3((unsigned)grid), dim3(256), 0, stream, c);
+  }
   if (c.nsplit > 1) {
     const int64_t rows = (int64_t)p->B * p->W * p->Hq;
     const unsigned mgrid = (unsigned)((rows + 3) / 4);
