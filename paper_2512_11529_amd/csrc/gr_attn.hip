@@ -23,7 +23,6 @@ typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 
 constexpr int KT = 64;        // kv tokens per LDS tile
-constexpr int PAD = 16;       // bf16 elements of row padding (32 B): conflict-free b128 and tr-b64 reads
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 
@@ -50,17 +49,116 @@ __device__ __forceinline__ float bf16_bits_to_float(uint32_t h) { return __uint_
 
 __device__ __forceinline__ bf16x8 as_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8, v); }
 
+// Per-tile building blocks.  A tile is KT = 64 prompt tokens; S^T of a tile is [64 kv x 32*NCB q]
+// = 2 sub-tiles x NCB column blocks of 32x32 fp32 accumulators.
+template <int D, int NCB>
+struct AttnTile {
+  static constexpr int KSTR = D + 8;     // K rows: +16 B  -> ds_read_b128 of 32 consecutive rows is conflict-free
+  static constexpr int VSTR = D + 16;    // V rows: +32 B  -> ds_read_b64_tr_b16 of 4-row groups is conflict-free
+
+  // S^T = K . Q^T from the K tile in LDS (A operand) and Q in registers (B operand)
+  static __device__ __forceinline__ void qk(const uint16_t* sk, const bf16x8 (&qop)[NCB][D / 16], f32x16 (&s)[KT / 32][NCB],
+                                            int n32, int G) {
+#pragma unroll
+    for (int sub = 0; sub < KT / 32; sub++)
+#pragma unroll
+      for (int cb = 0; cb < NCB; cb++)
+#pragma unroll
+        for (int i = 0; i < 16; i++) s[sub][cb][i] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < D / 16; ks++) {
+#pragma unroll
+      for (int sub = 0; sub < KT / 32; sub++) {
+        const bf16x8 a = as_bf16x8(*(const uint4*)(&sk[(sub * 32 + n32) * KSTR + ks * 16 + G * 8]));
+#pragma unroll
+        for (int cb = 0; cb < NCB; cb++) s[sub][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qop[cb][ks], s[sub][cb], 0, 0, 0);
+      }
+    }
+  }
+
+  // O^T += V^T . P^T.  V^T operand: d = 32*db + (lane%32), k slot e <-> token 16*s + 8*(e/4) + 4*G + e%4
+  static __device__ __forceinline__ void pv(const uint16_t* sv, const bf16x8 (&pop)[KT / 16][NCB], f32x16 (&o)[D / 32][NCB], int lane) {
+    const int G = lane >> 5;
+#pragma unroll
+    for (int s = 0; s < KT / 16; s++) {
+#pragma unroll
+      for (int db = 0; db < D / 32; db++) {
+        const int vrow = s * 16 + 4 * G + ((lane & 15) >> 2);
+        const int vcol = db * 32 + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+        const uint16_t* p0 = &sv[vrow * VSTR + vcol];
+        s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p0));
+        s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p0 + 8 * VSTR));
+        typedef short s16x8 __attribute__((ext_vector_type(8)));
+        s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        const bf16x8 a = __builtin_bit_cast(bf16x8, both);
+#pragma unroll
+        for (int cb = 0; cb < NCB; cb++) o[db][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pop[s][cb], o[db][cb], 0, 0, 0);
+      }
+    }
+  }
+
+  // Online softmax of one tile, one query column per lane (its other half lives in lane^32).
+  // The running reference m_ref is only raised when some column of the wave exceeds it by more than
+  // kLazy (log2 units): exp2 arguments stay <= kLazy, which fp32 sums and bf16 P hold easily, and the
+  // O accumulators need rescaling only on those rare tiles.  Returns (per column block) whether O
+  // must be multiplied by alpha[cb].
+  static constexpr float kLazy = 8.0f;
+  static __device__ __forceinline__ void softmax(f32x16 (&s)[KT / 32][NCB], bf16x8 (&pop)[KT / 16][NCB], float (&m_ref)[NCB],
+                                                 float (&l_run)[NCB], float (&alpha)[NCB], bool (&upd)[NCB], float c) {
+#pragma unroll
+    for (int cb = 0; cb < NCB; cb++) {
+      float mx = s[0][cb][0];
+#pragma unroll
+      for (int sub = 0; sub < KT / 32; sub++)
+#pragma unroll
+        for (int i = 0; i < 16; i++) mx = fmaxf(mx, s[sub][cb][i]);
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      upd[cb] = __any(mx * c > m_ref[cb] * c + kLazy);
+      const float m_new = upd[cb] ? fmaxf(m_ref[cb], mx) : m_ref[cb];
+      alpha[cb] = __builtin_amdgcn_exp2f((m_ref[cb] - m_new) * c);
+      const float mc = m_new * c;
+      float rs = 0.f;
+#pragma unroll
+      for (int sub = 0; sub < KT / 32; sub++)
+#pragma unroll
+        for (int i = 0; i < 16; i++) {
+          const float p = __builtin_amdgcn_exp2f(fmaf(s[sub][cb][i], c, -mc));
+          s[sub][cb][i] = p;
+          rs += p;
+        }
+      l_run[cb] = l_run[cb] * alpha[cb] + rs;
+      m_ref[cb] = m_new;
+      // P^T as B operands: slab t = accumulator registers 8*(t%2) .. +7 of sub-tile t/2
+#pragma unroll
+      for (int t = 0; t < KT / 16; t++) {
+        bf16x8 pvv;
+#pragma unroll
+        for (int e = 0; e < 8; e += 2) {
+          f32x2 two = {s[t / 2][cb][8 * (t % 2) + e], s[t / 2][cb][8 * (t % 2) + e + 1]};
+          bf16x2 h = __builtin_convertvector(two, bf16x2);
+          pvv[e] = h[0];
+          pvv[e + 1] = h[1];
+        }
+        pop[t][cb] = pvv;
+      }
+    }
+  }
+};
+
 template <int D, int NCB, int NWAVES>
 __global__ void __launch_bounds__(NWAVES * 64) k_beam_attn(AttnCtx c) {
+  using T = AttnTile<D, NCB>;
   constexpr int NT = NWAVES * 64;
   constexpr int MWG = NWAVES * 32 * NCB;
-  constexpr int LDS_STRIDE = D + PAD;            // bf16 elements per LDS row
+  constexpr int KSTR = T::KSTR, VSTR = T::VSTR;
   constexpr int PIECES = KT * D / 8;             // 16-byte pieces per tile
   constexpr int PPT = PIECES / NT;               // pieces per thread
   constexpr int PPR = D / 8;                     // pieces per row
   static_assert(PIECES % NT == 0, "tile must divide over the threads");
-  __shared__ __attribute__((aligned(16))) uint16_t s_k[KT * LDS_STRIDE];
-  __shared__ __attribute__((aligned(16))) uint16_t s_v[KT * LDS_STRIDE];
+  // double-buffered tiles: K(j) in s_k[j%2], V(j) in s_v[j%2]
+  extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
+  uint16_t* s_k = smem;
+  uint16_t* s_v = smem + 2 * KT * KSTR;
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, G = lane >> 5, n32 = lane & 31;
 
@@ -110,139 +208,84 @@ __global__ void __launch_bounds__(NWAVES * 64) k_beam_attn(AttnCtx c) {
 #pragma unroll
   for (int cb = 0; cb < NCB; cb++) { m_run[cb] = -INFINITY; l_run[cb] = 0.f; }
 
-  // ---- K/V tile staging
+  // ---- K/V tile staging: global -> registers (one tile ahead) -> LDS
   const uint16_t* kbase = c.ks + ((size_t)row0 * c.Hkv + kvh) * D;
   const uint16_t* vbase = c.vs + ((size_t)row0 * c.Hkv + kvh) * D;
   const size_t tok_stride = (size_t)c.Hkv * D;
   uint4 kreg[PPT], vreg[PPT];
-  auto load_tile = [&](int t) {
+  auto gload = [&](const uint16_t* base, int t, uint4 (&reg)[PPT]) {
     const int tok0 = seg0 + t * KT;
 #pragma unroll
     for (int i = 0; i < PPT; i++) {
       const int p = tid + i * NT;
-      const int r = p / PPR, col = (p % PPR) * 8;
-      const int tok = tok0 + r;
-      uint4 kv = make_uint4(0, 0, 0, 0), vv = make_uint4(0, 0, 0, 0);
-      if (tok < seg1) {
-        kv = *(const uint4*)(kbase + (size_t)tok * tok_stride + col);
-        vv = *(const uint4*)(vbase + (size_t)tok * tok_stride + col);
-      }
-      kreg[i] = kv;
-      vreg[i] = vv;
+      const int tok = tok0 + p / PPR;
+      reg[i] = make_uint4(0, 0, 0, 0);                     // rows past the segment read as zeros
+      if (tok < seg1) reg[i] = *(const uint4*)(base + (size_t)tok * tok_stride + (p % PPR) * 8);
     }
   };
-  auto store_tile = [&]() {
+  auto lstore = [&](uint16_t* dst, int stride, const uint4 (&reg)[PPT]) {
 #pragma unroll
     for (int i = 0; i < PPT; i++) {
       const int p = tid + i * NT;
-      const int r = p / PPR, col = (p % PPR) * 8;
-      *(uint4*)(&s_k[r * LDS_STRIDE + col]) = kreg[i];
-      *(uint4*)(&s_v[r * LDS_STRIDE + col]) = vreg[i];
+      *(uint4*)(&dst[(p / PPR) * stride + (p % PPR) * 8]) = reg[i];
     }
   };
 
-  if (ntiles > 0) load_tile(0);
-  for (int t = 0; t < ntiles; t++) {
+  if (ntiles > 0) {
+    // Pipeline: iteration t issues S(t+1) = K(t+1).Q^T together with the softmax of S(t), then O += V(t).P(t).
+    // K(t+2) and V(t+1) are written to LDS right after the barrier that opens iteration t, so one
+    // barrier per tile orders every buffer reuse.
+    gload(kbase, 0, kreg); gload(vbase, 0, vreg);
+    lstore(s_k, KSTR, kreg); lstore(s_v, VSTR, vreg);
+    if (ntiles > 1) { gload(kbase, 1, kreg); lstore(s_k + KT * KSTR, KSTR, kreg); }
+    if (ntiles > 2) gload(kbase, 2, kreg);
+    if (ntiles > 1) gload(vbase, 1, vreg);
     __syncthreads();
-    store_tile();
-    __syncthreads();
-    if (t + 1 < ntiles) load_tile(t + 1);
-
-    // ---- S^T = K . Q^T for the 64-token tile: two 32-token sub-tiles x NCB column blocks
-    f32x16 s_acc[KT / 32][NCB];
+    f32x16 s_cur[KT / 32][NCB];
+    T::qk(s_k, qop, s_cur, n32, G);
+    for (int t = 0; t < ntiles; t++) {
+      __syncthreads();
+      if (t + 2 < ntiles) lstore(s_k + (t & 1) * KT * KSTR, KSTR, kreg);
+      if (t + 1 < ntiles) lstore(s_v + ((t + 1) & 1) * KT * VSTR, VSTR, vreg);
+      if (t + 3 < ntiles) gload(kbase, t + 3, kreg);
+      if (t + 2 < ntiles) gload(vbase, t + 2, vreg);
+      const int tok0 = seg0 + t * KT;
+      if (tok0 + KT > seg1) {
+        // tokens past the end of the segment do not exist
 #pragma unroll
-    for (int sub = 0; sub < KT / 32; sub++)
+        for (int sub = 0; sub < KT / 32; sub++)
+#pragma unroll
+          for (int i = 0; i < 16; i++) {
+            const int kv = tok0 + sub * 32 + 8 * (i / 4) + 4 * G + (i % 4);
+            if (kv >= seg1) {
+#pragma unroll
+              for (int cb = 0; cb < NCB; cb++) s_cur[sub][cb][i] = -INFINITY;
+            }
+          }
+      }
+      bf16x8 pop[KT / 16][NCB];
+      float alpha[NCB];
+      bool upd[NCB];
+      if (t + 1 < ntiles) {
+        f32x16 s_next[KT / 32][NCB];
+        T::qk(s_k + ((t + 1) & 1) * KT * KSTR, qop, s_next, n32, G);
+        T::softmax(s_cur, pop, m_run, l_run, alpha, upd, c.c);
+#pragma unroll
+        for (int sub = 0; sub < KT / 32; sub++)
+#pragma unroll
+          for (int cb = 0; cb < NCB; cb++) s_cur[sub][cb] = s_next[sub][cb];
+      } else {
+        T::softmax(s_cur, pop, m_run, l_run, alpha, upd, c.c);
+      }
 #pragma unroll
       for (int cb = 0; cb < NCB; cb++)
+        if (upd[cb]) {
 #pragma unroll
-        for (int i = 0; i < 16; i++) s_acc[sub][cb][i] = 0.f;
+          for (int db = 0; db < D / 32; db++)
 #pragma unroll
-    for (int ks = 0; ks < D / 16; ks++) {
-#pragma unroll
-      for (int sub = 0; sub < KT / 32; sub++) {
-        const bf16x8 a = as_bf16x8(*(const uint4*)(&s_k[(sub * 32 + n32) * LDS_STRIDE + ks * 16 + G * 8]));
-#pragma unroll
-        for (int cb = 0; cb < NCB; cb++)
-          s_acc[sub][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qop[cb][ks], s_acc[sub][cb], 0, 0, 0);
-      }
-    }
-    // tokens past the end of the segment do not exist
-    const int tok0 = seg0 + t * KT;
-    if (tok0 + KT > seg1) {
-#pragma unroll
-      for (int sub = 0; sub < KT / 32; sub++)
-#pragma unroll
-        for (int i = 0; i < 16; i++) {
-          const int kv = tok0 + sub * 32 + 8 * (i / 4) + 4 * G + (i % 4);
-          if (kv >= seg1) {
-#pragma unroll
-            for (int cb = 0; cb < NCB; cb++) s_acc[sub][cb][i] = -INFINITY;
-          }
+            for (int i = 0; i < 16; i++) o_acc[db][cb][i] *= alpha[cb];
         }
-    }
-
-    // ---- online softmax, one query column per lane (the other half of the column is in lane^32)
-    bf16x8 pop[KT / 16][NCB];
-#pragma unroll
-    for (int cb = 0; cb < NCB; cb++) {
-      float mx = s_acc[0][cb][0];
-#pragma unroll
-      for (int sub = 0; sub < KT / 32; sub++)
-#pragma unroll
-        for (int i = 0; i < 16; i++) mx = fmaxf(mx, s_acc[sub][cb][i]);
-      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-      const float m_new = fmaxf(m_run[cb], mx);
-      const float alpha = __builtin_amdgcn_exp2f((m_run[cb] - m_new) * c.c);
-      const float mc = m_new * c.c;
-      float rs = 0.f;
-#pragma unroll
-      for (int sub = 0; sub < KT / 32; sub++)
-#pragma unroll
-        for (int i = 0; i < 16; i++) {
-          const float p = __builtin_amdgcn_exp2f(fmaf(s_acc[sub][cb][i], c.c, -mc));
-          s_acc[sub][cb][i] = p;
-          rs += p;
-        }
-      l_run[cb] = l_run[cb] * alpha + rs;
-      m_run[cb] = m_new;
-      if (__any(alpha != 1.0f)) {
-#pragma unroll
-        for (int db = 0; db < D / 32; db++)
-#pragma unroll
-          for (int i = 0; i < 16; i++) o_acc[db][cb][i] *= alpha;
-      }
-      // P^T as B operands: slab s = accumulator registers 8*(s%2) .. +7 of sub-tile s/2
-#pragma unroll
-      for (int s = 0; s < KT / 16; s++) {
-        bf16x8 pv;
-#pragma unroll
-        for (int e = 0; e < 8; e += 2) {
-          f32x2 two = {s_acc[s / 2][cb][8 * (s % 2) + e], s_acc[s / 2][cb][8 * (s % 2) + e + 1]};
-          bf16x2 h = __builtin_convertvector(two, bf16x2);
-          pv[e] = h[0];
-          pv[e + 1] = h[1];
-        }
-        pop[s][cb] = pv;
-      }
-    }
-
-    // ---- O^T += V^T . P^T.  V^T operand: d = 32*db + (lane%32), k slot e <-> token 16*s + 8*(e/4) + 4*G + e%4
-#pragma unroll
-    for (int s = 0; s < KT / 16; s++) {
-#pragma unroll
-      for (int db = 0; db < D / 32; db++) {
-        const int vrow = s * 16 + 4 * G + ((lane & 15) >> 2);
-        const int vcol = db * 32 + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
-        const uint16_t* p0 = &s_v[vrow * LDS_STRIDE + vcol];
-        s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p0));
-        s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p0 + 8 * LDS_STRIDE));
-        typedef short s16x8 __attribute__((ext_vector_type(8)));
-        s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-        const bf16x8 a = __builtin_bit_cast(bf16x8, both);
-#pragma unroll
-        for (int cb = 0; cb < NCB; cb++)
-          o_acc[db][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pop[s][cb], o_acc[db][cb], 0, 0, 0);
-      }
+      T::pv(s_v + (t & 1) * KT * VSTR, pop, o_acc, lane);
     }
   }
 
@@ -360,7 +403,7 @@ __global__ void __launch_bounds__(256) k_attn_merge(AttnCtx c) {
 
 constexpr int kMWG = 256;
 #include <cstdlib>
-static int attn_variant() { const char* e = getenv("GR_ATTN_VARIANT"); return e ? atoi(e) : 0; }
+static int attn_variant() { const char* e = getenv("GR_ATTN_VARIANT"); return e ? atoi(e) : 1; }
 
 int choose_nsplit(const gr_attn_params* p) {
   const int g = p->Hq / p->Hkv;
@@ -423,13 +466,18 @@ extern "C" gr_status gr_beam_attn(const gr_attn_params* p, void* workspace, size
   const int64_t grid = groups_padded * c.MB;
   if (grid >= ((int64_t)1 << 31)) return GR_ERR_UNSUPPORTED;
   const int var = attn_variant();
+  const size_t lds = (size_t)2 * KT * ((p->d + 8) + (p->d + 16)) * 2;
+#define GR_LAUNCH_ATTN(DD, NCB_, NW_)                                                                                        \
+  do {                                                                                                                       \
+    GR_HIP_TRY(hipFuncSetAttribute((const void*)k_beam_attn<DD, NCB_, NW_>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)); \
+    hipLaunchKernelGGL((k_beam_attn<DD, NCB_, NW_>), dim3((unsigned)grid), dim3(NW_ * 64), lds, stream, c);                  \
+  } while (0)
   if (p->d == 128) {
-    if (var == 1) hipLaunchKernelGGL((k_beam_attn<128, 1, 8>), dim3((unsigned)grid), dim3(512), 0, stream, c);
-    else hipLaunchKernelGGL((k_beam_attn<128, 2, 4>), dim3((unsigned)grid), dim3(256), 0, stream, c);
+    if (var == 1) GR_LAUNCH_ATTN(128, 1, 8); else GR_LAUNCH_ATTN(128, 2, 4);
   } else {
-    if (var == 1) hipLaunchKernelGGL((k_beam_attn<64, 1, 8>), dim3((unsigned)grid), dim3(512), 0, stream, c);
-    else hipLaunchKernelGGL((k_beam_attn<64, 2, 4>), dim3((unsigned)grid), dim3(256), 0, stream, c);
+    if (var == 1) GR_LAUNCH_ATTN(64, 1, 8); else GR_LAUNCH_ATTN(64, 2, 4);
   }
+#undef GR_LAUNCH_ATTN
   if (c.nsplit > 1) {
     const int64_t rows = (int64_t)p->B * p->W * p->Hq;
     const unsigned mgrid = (unsigned)((rows + 3) / 4);
