@@ -152,7 +152,7 @@ def main():
     if not args.no_cpu_baseline:
         import oracle
         oracle.build()
-        nb = args.cpu_sample_requests or max(1, min(B, {1: 1, 2: 4, 3: 2, 4: 1, 5: 2}.get(cfg.config_id, 1)))
+        nb = args.cpu_sample_requests or max(1, min(B, {1: 1, 2: 8, 3: 8, 4: 1, 5: 8}.get(cfg.config_id, 1)))
         t_cpu = time.perf_counter()
         sc, pf, _ = gr_synth.initial_beam_state(nb, W, ND)
         n_steps_cpu = 1 if cfg.config_id == 4 else ND      # the long-prompt shape: one step is already ~20 s
