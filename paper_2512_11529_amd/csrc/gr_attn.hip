@@ -65,36 +65,56 @@ struct AttnTile {
       for (int cb = 0; cb < NCB; cb++)
 #pragma unroll
         for (int i = 0; i < 16; i++) s[sub][cb][i] = 0.f;
+    // operand reads run PF steps ahead of the MFMAs that consume them
+    constexpr int N = (KT / 32) * (D / 16), PF = 8;
+    bf16x8 a[N];
 #pragma unroll
-    for (int ks = 0; ks < D / 16; ks++) {
+    for (int i = 0; i < PF; i++) a[i] = as_bf16x8(*(const uint4*)(&sk[((i % 2) * 32 + n32) * KSTR + (i / 2) * 16 + G * 8]));
 #pragma unroll
-      for (int sub = 0; sub < KT / 32; sub++) {
-        const bf16x8 a = as_bf16x8(*(const uint4*)(&sk[(sub * 32 + n32) * KSTR + ks * 16 + G * 8]));
+    for (int i = 0; i < N; i++) {
+      if (i + PF < N) a[i + PF] = as_bf16x8(*(const uint4*)(&sk[(((i + PF) % 2) * 32 + n32) * KSTR + ((i + PF) / 2) * 16 + G * 8]));
 #pragma unroll
-        for (int cb = 0; cb < NCB; cb++) s[sub][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qop[cb][ks], s[sub][cb], 0, 0, 0);
-      }
+      for (int cb = 0; cb < NCB; cb++) s[i % 2][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], qop[cb][i / 2], s[i % 2][cb], 0, 0, 0);
     }
+    __builtin_amdgcn_sched_group_barrier(0x100, PF, 0);
+#pragma unroll
+    for (int i = 0; i < N - PF; i++) {
+      __builtin_amdgcn_sched_group_barrier(0x008, NCB, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+    }
+    __builtin_amdgcn_sched_group_barrier(0x008, PF * NCB, 0);
   }
 
   // O^T += V^T . P^T.  V^T operand: d = 32*db + (lane%32), k slot e <-> token 16*s + 8*(e/4) + 4*G + e%4
   static __device__ __forceinline__ void pv(const uint16_t* sv, const bf16x8 (&pop)[KT / 16][NCB], f32x16 (&o)[D / 32][NCB], int lane) {
     const int G = lane >> 5;
+    typedef short s16x8 __attribute__((ext_vector_type(8)));
+    constexpr int N = (KT / 16) * (D / 32), PF = 4;      // operand i: slab i / (D/32), d block i % (D/32)
+    const uint16_t* base = sv + (4 * G + ((lane & 15) >> 2)) * VSTR + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+    auto rd = [&](int i) {
+      const uint16_t* p0 = base + (i / (D / 32)) * 16 * VSTR + (i % (D / 32)) * 32;
+      s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p0));
+      s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p0 + 8 * VSTR));
+      s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+      return __builtin_bit_cast(bf16x8, both);
+    };
+    bf16x8 a[N];
 #pragma unroll
-    for (int s = 0; s < KT / 16; s++) {
+    for (int i = 0; i < PF; i++) a[i] = rd(i);
 #pragma unroll
-      for (int db = 0; db < D / 32; db++) {
-        const int vrow = s * 16 + 4 * G + ((lane & 15) >> 2);
-        const int vcol = db * 32 + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
-        const uint16_t* p0 = &sv[vrow * VSTR + vcol];
-        s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p0));
-        s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p0 + 8 * VSTR));
-        typedef short s16x8 __attribute__((ext_vector_type(8)));
-        s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-        const bf16x8 a = __builtin_bit_cast(bf16x8, both);
+    for (int i = 0; i < N; i++) {
+      if (i + PF < N) a[i + PF] = rd(i + PF);
 #pragma unroll
-        for (int cb = 0; cb < NCB; cb++) o[db][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pop[s][cb], o[db][cb], 0, 0, 0);
-      }
+      for (int cb = 0; cb < NCB; cb++)
+        o[i % (D / 32)][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], pop[i / (D / 32)][cb], o[i % (D / 32)][cb], 0, 0, 0);
     }
+    __builtin_amdgcn_sched_group_barrier(0x100, 2 * PF, 1);
+#pragma unroll
+    for (int i = 0; i < N - PF; i++) {
+      __builtin_amdgcn_sched_group_barrier(0x008, NCB, 1);
+      __builtin_amdgcn_sched_group_barrier(0x100, 2, 1);
+    }
+    __builtin_amdgcn_sched_group_barrier(0x008, PF * NCB, 1);
   }
 
   // Online softmax of one tile, one query column per lane (its other half lives in lane^32).
@@ -146,7 +166,8 @@ struct AttnTile {
 };
 
 template <int D, int NCB, int NWAVES>
-__global__ void __launch_bounds__(NWAVES * 64) k_beam_attn(AttnCtx c) {
+__global__ void __launch_bounds__(NWAVES * 64) __attribute__((amdgpu_waves_per_eu(NCB == 1 ? 2 : 1, NCB == 1 ? 2 : 1)))
+k_beam_attn(AttnCtx c) {
   using T = AttnTile<D, NCB>;
   constexpr int NT = NWAVES * 64;
   constexpr int MWG = NWAVES * 32 * NCB;
@@ -211,35 +232,40 @@ __global__ void __launch_bounds__(NWAVES * 64) k_beam_attn(AttnCtx c) {
   // ---- K/V tile staging: global -> registers (one tile ahead) -> LDS
   const uint16_t* kbase = c.ks + ((size_t)row0 * c.Hkv + kvh) * D;
   const uint16_t* vbase = c.vs + ((size_t)row0 * c.Hkv + kvh) * D;
-  const size_t tok_stride = (size_t)c.Hkv * D;
-  uint4 kreg[PPT], vreg[PPT];
-  auto gload = [&](const uint16_t* base, int t, uint4 (&reg)[PPT]) {
+  const int tok_stride = c.Hkv * D;                       // elements between consecutive tokens
+  struct Stage { uint4 r[PPT]; };
+  Stage kreg, vreg;
+  int prow[PPT], pcol[PPT];                               // this thread's 16-byte pieces of a tile (loop invariant)
+#pragma unroll
+  for (int i = 0; i < PPT; i++) { const int p = tid + i * NT; prow[i] = p / PPR; pcol[i] = (p % PPR) * 8; }
+  // Rows past the end of the segment re-read its last row: finite data that the -inf score mask
+  // (K side) and the zero probabilities (V side) make irrelevant, and no branch in the load path.
+  auto gload = [&](const uint16_t* base, int t) {
     const int tok0 = seg0 + t * KT;
+    const int last = seg1 - tok0 - 1;
+    const uint16_t* tile = base + (size_t)tok0 * tok_stride;   // wave-uniform
+    Stage st;
 #pragma unroll
-    for (int i = 0; i < PPT; i++) {
-      const int p = tid + i * NT;
-      const int tok = tok0 + p / PPR;
-      reg[i] = make_uint4(0, 0, 0, 0);                     // rows past the segment read as zeros
-      if (tok < seg1) reg[i] = *(const uint4*)(base + (size_t)tok * tok_stride + (p % PPR) * 8);
-    }
+    for (int i = 0; i < PPT; i++) st.r[i] = *(const uint4*)(tile + min(prow[i], last) * tok_stride + pcol[i]);
+    return st;
   };
-  auto lstore = [&](uint16_t* dst, int stride, const uint4 (&reg)[PPT]) {
+  auto lstore = [&](uint16_t* dst, int stride, const Stage& st) {
 #pragma unroll
-    for (int i = 0; i < PPT; i++) {
-      const int p = tid + i * NT;
-      *(uint4*)(&dst[(p / PPR) * stride + (p % PPR) * 8]) = reg[i];
-    }
+    for (int i = 0; i < PPT; i++) *(uint4*)(&dst[prow[i] * stride + pcol[i]]) = st.r[i];
   };
 
   if (ntiles > 0) {
     // Pipeline: iteration t issues S(t+1) = K(t+1).Q^T together with the softmax of S(t), then O += V(t).P(t).
     // K(t+2) and V(t+1) are written to LDS right after the barrier that opens iteration t, so one
     // barrier per tile orders every buffer reuse.
-    gload(kbase, 0, kreg); gload(vbase, 0, vreg);
+    // loads for tiles past the end are clamped to the last tile (harmless re-reads, never stored)
+    const int tl = ntiles - 1;
+    kreg = gload(kbase, 0); vreg = gload(vbase, 0);
+    Stage k1 = gload(kbase, min(1, tl));
     lstore(s_k, KSTR, kreg); lstore(s_v, VSTR, vreg);
-    if (ntiles > 1) { gload(kbase, 1, kreg); lstore(s_k + KT * KSTR, KSTR, kreg); }
-    if (ntiles > 2) gload(kbase, 2, kreg);
-    if (ntiles > 1) gload(vbase, 1, vreg);
+    lstore(s_k + KT * KSTR, KSTR, k1);
+    kreg = gload(kbase, min(2, tl));
+    vreg = gload(vbase, min(1, tl));
     __syncthreads();
     f32x16 s_cur[KT / 32][NCB];
     T::qk(s_k, qop, s_cur, n32, G);
@@ -247,8 +273,8 @@ __global__ void __launch_bounds__(NWAVES * 64) k_beam_attn(AttnCtx c) {
       __syncthreads();
       if (t + 2 < ntiles) lstore(s_k + (t & 1) * KT * KSTR, KSTR, kreg);
       if (t + 1 < ntiles) lstore(s_v + ((t + 1) & 1) * KT * VSTR, VSTR, vreg);
-      if (t + 3 < ntiles) gload(kbase, t + 3, kreg);
-      if (t + 2 < ntiles) gload(vbase, t + 2, vreg);
+      kreg = gload(kbase, min(t + 3, tl));
+      vreg = gload(vbase, min(t + 2, tl));
       const int tok0 = seg0 + t * KT;
       if (tok0 + KT > seg1) {
         // tokens past the end of the segment do not exist
@@ -401,9 +427,10 @@ __global__ void __launch_bounds__(256) k_attn_merge(AttnCtx c) {
   if (c.lse && lane == 0) c.lse[row] = (L > 0.f) ? (M2 + __builtin_amdgcn_logf(L)) * kLn2 : -INFINITY;
 }
 
-constexpr int kMWG = 256;
 #include <cstdlib>
 static int attn_variant() { const char* e = getenv("GR_ATTN_VARIANT"); return e ? atoi(e) : 1; }
+static int attn_mwg() { return attn_variant() == 2 ? 128 : 256; }
+#define kMWG attn_mwg()
 
 int choose_nsplit(const gr_attn_params* p) {
   const int g = p->Hq / p->Hkv;
@@ -473,9 +500,9 @@ extern "C" gr_status gr_beam_attn(const gr_attn_params* p, void* workspace, size
     hipLaunchKernelGGL((k_beam_attn<DD, NCB_, NW_>), dim3((unsigned)grid), dim3(NW_ * 64), lds, stream, c);                  \
   } while (0)
   if (p->d == 128) {
-    if (var == 1) GR_LAUNCH_ATTN(128, 1, 8); else GR_LAUNCH_ATTN(128, 2, 4);
+    if (var == 1) GR_LAUNCH_ATTN(128, 1, 8); else if (var == 2) GR_LAUNCH_ATTN(128, 1, 4); else GR_LAUNCH_ATTN(128, 2, 4);
   } else {
-    if (var == 1) GR_LAUNCH_ATTN(64, 1, 8); else GR_LAUNCH_ATTN(64, 2, 4);
+    if (var == 1) GR_LAUNCH_ATTN(64, 1, 8); else if (var == 2) GR_LAUNCH_ATTN(64, 1, 4); else GR_LAUNCH_ATTN(64, 2, 4);
   }
 #undef GR_LAUNCH_ATTN
   if (c.nsplit > 1) {
