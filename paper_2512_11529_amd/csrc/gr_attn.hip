@@ -66,7 +66,7 @@ struct AttnTile {
 #pragma unroll
         for (int i = 0; i < 16; i++) s[sub][cb][i] = 0.f;
     // operand reads run PF steps ahead of the MFMAs that consume them
-    constexpr int N = (KT / 32) * (D / 16), PF = 8;
+    constexpr int N = (KT / 32) * (D / 16), PF = 4;
     bf16x8 a[N];
 #pragma unroll
     for (int i = 0; i < PF; i++) a[i] = as_bf16x8(*(const uint4*)(&sk[((i % 2) * 32 + n32) * KSTR + (i / 2) * 16 + G * 8]));
@@ -257,8 +257,8 @@ k_beam_attn(AttnCtx c) {
   if (ntiles > 0) {
     // Pipeline: iteration t issues S(t+1) = K(t+1).Q^T together with the softmax of S(t), then O += V(t).P(t).
     // K(t+2) and V(t+1) are written to LDS right after the barrier that opens iteration t, so one
-    // barrier per tile orders every buffer reuse.
-    // loads for tiles past the end are clamped to the last tile (harmless re-reads, never stored)
+    // barrier per tile orders every buffer reuse.  Loads for tiles past the end are clamped to the
+    // last tile (harmless re-reads; a duplicate K tile lands in a buffer nobody reads any more).
     const int tl = ntiles - 1;
     kreg = gload(kbase, 0); vreg = gload(vbase, 0);
     Stage k1 = gload(kbase, min(1, tl));
@@ -267,42 +267,8 @@ k_beam_attn(AttnCtx c) {
     kreg = gload(kbase, min(2, tl));
     vreg = gload(vbase, min(1, tl));
     __syncthreads();
-    f32x16 s_cur[KT / 32][NCB];
-    T::qk(s_k, qop, s_cur, n32, G);
-    for (int t = 0; t < ntiles; t++) {
-      __syncthreads();
-      if (t + 2 < ntiles) lstore(s_k + (t & 1) * KT * KSTR, KSTR, kreg);
-      if (t + 1 < ntiles) lstore(s_v + ((t + 1) & 1) * KT * VSTR, VSTR, vreg);
-      kreg = gload(kbase, min(t + 3, tl));
-      vreg = gload(vbase, min(t + 2, tl));
-      const int tok0 = seg0 + t * KT;
-      if (tok0 + KT > seg1) {
-        // tokens past the end of the segment do not exist
-#pragma unroll
-        for (int sub = 0; sub < KT / 32; sub++)
-#pragma unroll
-          for (int i = 0; i < 16; i++) {
-            const int kv = tok0 + sub * 32 + 8 * (i / 4) + 4 * G + (i % 4);
-            if (kv >= seg1) {
-#pragma unroll
-              for (int cb = 0; cb < NCB; cb++) s_cur[sub][cb][i] = -INFINITY;
-            }
-          }
-      }
-      bf16x8 pop[KT / 16][NCB];
-      float alpha[NCB];
-      bool upd[NCB];
-      if (t + 1 < ntiles) {
-        f32x16 s_next[KT / 32][NCB];
-        T::qk(s_k + ((t + 1) & 1) * KT * KSTR, qop, s_next, n32, G);
-        T::softmax(s_cur, pop, m_run, l_run, alpha, upd, c.c);
-#pragma unroll
-        for (int sub = 0; sub < KT / 32; sub++)
-#pragma unroll
-          for (int cb = 0; cb < NCB; cb++) s_cur[sub][cb] = s_next[sub][cb];
-      } else {
-        T::softmax(s_cur, pop, m_run, l_run, alpha, upd, c.c);
-      }
+
+    auto rescale = [&](const float (&alpha)[NCB], const bool (&upd)[NCB]) {
 #pragma unroll
       for (int cb = 0; cb < NCB; cb++)
         if (upd[cb]) {
@@ -311,7 +277,56 @@ k_beam_attn(AttnCtx c) {
 #pragma unroll
             for (int i = 0; i < 16; i++) o_acc[db][cb][i] *= alpha[cb];
         }
+    };
+    // one steady-state iteration: tile t (scores in s_in) has a successor whose scores go to s_out
+    auto step = [&](f32x16 (&s_in)[KT / 32][NCB], f32x16 (&s_out)[KT / 32][NCB], int t) {
+      __syncthreads();
+      lstore(s_k + (t & 1) * KT * KSTR, KSTR, kreg);                 // K(t+2)
+      lstore(s_v + ((t + 1) & 1) * KT * VSTR, VSTR, vreg);           // V(t+1)
+      kreg = gload(kbase, min(t + 3, tl));
+      vreg = gload(vbase, min(t + 2, tl));
+      bf16x8 pop[KT / 16][NCB];
+      float alpha[NCB];
+      bool upd[NCB];
+      T::qk(s_k + ((t + 1) & 1) * KT * KSTR, qop, s_out, n32, G);
+      T::softmax(s_in, pop, m_run, l_run, alpha, upd, c.c);
+      rescale(alpha, upd);
       T::pv(s_v + (t & 1) * KT * VSTR, pop, o_acc, lane);
+    };
+    // the last tile of the segment: the only one that can be partial, and it has no successor
+    auto last = [&](f32x16 (&s_in)[KT / 32][NCB], int t) {
+      __syncthreads();
+      const int tok0 = seg0 + t * KT;
+      if (tok0 + KT > seg1) {
+#pragma unroll
+        for (int sub = 0; sub < KT / 32; sub++)
+#pragma unroll
+          for (int i = 0; i < 16; i++) {
+            const int kv = tok0 + sub * 32 + 8 * (i / 4) + 4 * G + (i % 4);
+#pragma unroll
+            for (int cb = 0; cb < NCB; cb++) s_in[sub][cb][i] = (kv >= seg1) ? -INFINITY : s_in[sub][cb][i];
+          }
+      }
+      bf16x8 pop[KT / 16][NCB];
+      float alpha[NCB];
+      bool upd[NCB];
+      T::softmax(s_in, pop, m_run, l_run, alpha, upd, c.c);
+      rescale(alpha, upd);
+      T::pv(s_v + (t & 1) * KT * VSTR, pop, o_acc, lane);
+    };
+
+    f32x16 s_a[KT / 32][NCB], s_b[KT / 32][NCB];      // ping-pong score accumulators: no copies
+    T::qk(s_k, qop, s_a, n32, G);
+    int t = 0;
+    for (; t + 2 < ntiles; t += 2) {
+      step(s_a, s_b, t);
+      step(s_b, s_a, t + 1);
+    }
+    if (t + 1 < ntiles) {
+      step(s_a, s_b, t);
+      last(s_b, t + 1);
+    } else {
+      last(s_a, t);
     }
   }
 
@@ -324,39 +339,64 @@ k_beam_attn(AttnCtx c) {
     const int hq = kvh * c.g + j;
     float m = m_run[cb], l = l_run[cb];
     if (sp == 0) {
-      for (int ju = 0; ju < c.u; ju++) {
-        const size_t off = ((((size_t)b * c.W + w) * c.ND + ju) * c.Hkv + kvh) * D;
-        const uint16_t* kp = c.ku + off + G * 8;
-        float dot = 0.f;
+      // unshared stage: this beam's own u decode tokens, up to UCH at a time so that all of their
+      // K rows (then all of their V rows) are in flight together instead of one latency per token
+      constexpr int UCH = 4;
+      for (int j0 = 0; j0 < c.u; j0 += UCH) {
+        const size_t off0 = ((((size_t)b * c.W + w) * c.ND + j0) * c.Hkv + kvh) * D;
+        const size_t jstride = (size_t)c.Hkv * D;
+        float dot[UCH];
 #pragma unroll
-        for (int ks = 0; ks < D / 16; ks++) {
-          const uint4 kv = *(const uint4*)(kp + ks * 16);
-          const uint32_t kw[4] = {kv.x, kv.y, kv.z, kv.w};
+        for (int jj = 0; jj < UCH; jj++) {
+          dot[jj] = -INFINITY;
+          if (j0 + jj < c.u) {
+            const uint16_t* kp = c.ku + off0 + jj * jstride + G * 8;
+            uint4 kv[D / 16];
 #pragma unroll
-          for (int e = 0; e < 4; e++) {
-            dot = fmaf((float)qop[cb][ks][2 * e], bf16_bits_to_float(kw[e] & 0xffffu), dot);
-            dot = fmaf((float)qop[cb][ks][2 * e + 1], bf16_bits_to_float(kw[e] >> 16), dot);
+            for (int ks = 0; ks < D / 16; ks++) kv[ks] = *(const uint4*)(kp + ks * 16);
+            float acc = 0.f;
+#pragma unroll
+            for (int ks = 0; ks < D / 16; ks++) {
+              const uint32_t kw[4] = {kv[ks].x, kv[ks].y, kv[ks].z, kv[ks].w};
+#pragma unroll
+              for (int e = 0; e < 4; e++) {
+                acc = fmaf((float)qop[cb][ks][2 * e], bf16_bits_to_float(kw[e] & 0xffffu), acc);
+                acc = fmaf((float)qop[cb][ks][2 * e + 1], bf16_bits_to_float(kw[e] >> 16), acc);
+              }
+            }
+            dot[jj] = acc + __shfl_xor(acc, 32, 64);
           }
         }
-        dot += __shfl_xor(dot, 32, 64);
-        const float m_new = fmaxf(m, dot);
+        float m_new = m;
+#pragma unroll
+        for (int jj = 0; jj < UCH; jj++) m_new = fmaxf(m_new, dot[jj]);
         const float alpha = __builtin_amdgcn_exp2f((m - m_new) * c.c);
-        const float p = __builtin_amdgcn_exp2f((dot - m_new) * c.c);
-        l = l * alpha + (G == 0 ? p : 0.f);
+        float pj[UCH], psum = 0.f;
+#pragma unroll
+        for (int jj = 0; jj < UCH; jj++) { pj[jj] = __builtin_amdgcn_exp2f((dot[jj] - m_new) * c.c); psum += pj[jj]; }
+        l = l * alpha + (G == 0 ? psum : 0.f);
         m = m_new;
-        const uint16_t* vp = c.vu + off + 4 * G;
 #pragma unroll
         for (int db = 0; db < D / 32; db++)
 #pragma unroll
-          for (int q4 = 0; q4 < 4; q4++) {
-            const uint2 vv = *(const uint2*)(vp + db * 32 + 8 * q4);
-            const float v0 = bf16_bits_to_float(vv.x & 0xffffu), v1 = bf16_bits_to_float(vv.x >> 16);
-            const float v2 = bf16_bits_to_float(vv.y & 0xffffu), v3 = bf16_bits_to_float(vv.y >> 16);
-            o_acc[db][cb][4 * q4 + 0] = fmaf(p, v0, o_acc[db][cb][4 * q4 + 0] * alpha);
-            o_acc[db][cb][4 * q4 + 1] = fmaf(p, v1, o_acc[db][cb][4 * q4 + 1] * alpha);
-            o_acc[db][cb][4 * q4 + 2] = fmaf(p, v2, o_acc[db][cb][4 * q4 + 2] * alpha);
-            o_acc[db][cb][4 * q4 + 3] = fmaf(p, v3, o_acc[db][cb][4 * q4 + 3] * alpha);
+          for (int i = 0; i < 16; i++) o_acc[db][cb][i] *= alpha;
+#pragma unroll
+        for (int jj = 0; jj < UCH; jj++) {
+          if (j0 + jj < c.u) {
+            const uint16_t* vp = c.vu + off0 + jj * jstride + 4 * G;
+            uint2 vv[D / 8];
+#pragma unroll
+            for (int k = 0; k < D / 8; k++) vv[k] = *(const uint2*)(vp + (k / 4) * 32 + 8 * (k % 4));
+#pragma unroll
+            for (int k = 0; k < D / 8; k++) {
+              const int db = k / 4, q4 = k % 4;
+              o_acc[db][cb][4 * q4 + 0] = fmaf(pj[jj], bf16_bits_to_float(vv[k].x & 0xffffu), o_acc[db][cb][4 * q4 + 0]);
+              o_acc[db][cb][4 * q4 + 1] = fmaf(pj[jj], bf16_bits_to_float(vv[k].x >> 16), o_acc[db][cb][4 * q4 + 1]);
+              o_acc[db][cb][4 * q4 + 2] = fmaf(pj[jj], bf16_bits_to_float(vv[k].y & 0xffffu), o_acc[db][cb][4 * q4 + 2]);
+              o_acc[db][cb][4 * q4 + 3] = fmaf(pj[jj], bf16_bits_to_float(vv[k].y >> 16), o_acc[db][cb][4 * q4 + 3]);
+            }
           }
+        }
       }
     }
     const float l_tot = l + __shfl_xor(l, 32, 64);
