@@ -467,29 +467,33 @@ __global__ void __launch_bounds__(256) k_attn_merge(AttnCtx c) {
   if (c.lse && lane == 0) c.lse[row] = (L > 0.f) ? (M2 + __builtin_amdgcn_logf(L)) * kLn2 : -INFINITY;
 }
 
-#include <cstdlib>
-static int attn_variant() { const char* e = getenv("GR_ATTN_VARIANT"); return e ? atoi(e) : 1; }
-static int attn_mwg() { return attn_variant() == 2 ? 128 : 256; }
-#define kMWG attn_mwg()
-
-int choose_nsplit(const gr_attn_params* p) {
+// Host-side launch plan.  Big problems use 8-wave workgroups of 256 query rows (each K/V tile staged
+// once per 256 rows); small ones use 4-wave workgroups of 128 rows, two per CU, so that more units
+// exist and one workgroup's prologue overlaps the other's main loop.  When there are still too few
+// units to fill 256 CUs a few times over, the prompt is split into L segments (merged by k_attn_merge).
+struct AttnPlan { int mwg, nsplit; };
+AttnPlan plan_attn(const gr_attn_params* p) {
   const int g = p->Hq / p->Hkv;
-  const int MB = (p->W * g + kMWG - 1) / kMWG;
-  const int64_t units = (int64_t)p->B * p->Hkv * MB;
-  if (units >= 512 || p->max_L <= 4 * KT) return 1;
-  int64_t want = (1024 + units - 1) / units;
-  int64_t cap = p->max_L / (4 * KT);     // at least four tiles per segment
-  int64_t n = want < cap ? want : cap;
-  if (n > 16) n = 16;
-  if (n < 1) n = 1;
-  return (int)n;
+  const int64_t M = (int64_t)p->W * g;
+  const int64_t units256 = (int64_t)p->B * p->Hkv * ((M + 255) / 256);
+  AttnPlan plan;
+  plan.mwg = units256 >= 256 ? 256 : 128;
+  const int64_t units = (int64_t)p->B * p->Hkv * ((M + plan.mwg - 1) / plan.mwg);
+  plan.nsplit = 1;
+  if (units < 512 && p->max_L > 4 * KT) {
+    int64_t want = (1024 + units - 1) / units;
+    int64_t cap = p->max_L / (4 * KT);     // at least four tiles per segment
+    int64_t n = want < cap ? want : cap;
+    plan.nsplit = (int)(n > 16 ? 16 : (n < 1 ? 1 : n));
+  }
+  return plan;
 }
 
 }  // namespace
 
 extern "C" size_t gr_beam_attn_workspace_bytes(const gr_attn_params* p) {
   if (!p || p->B <= 0 || p->W <= 0 || p->Hq <= 0 || p->Hkv <= 0 || p->Hq % p->Hkv) return 0;
-  const int ns = choose_nsplit(p);
+  const int ns = plan_attn(p).nsplit;
   if (ns == 1) return 0;
   const size_t rows = (size_t)p->B * ns * p->W * p->Hq;
   return gr_align256(rows * p->d * 4) + gr_align256(rows * 8);
@@ -513,8 +517,9 @@ extern "C" gr_status gr_beam_attn(const gr_attn_params* p, void* workspace, size
   AttnCtx c;
   c.B = p->B; c.W = p->W; c.Hq = p->Hq; c.Hkv = p->Hkv; c.g = g; c.ND = p->ND; c.u = p->u;
   c.M = p->W * g;
-  c.MB = (c.M + kMWG - 1) / kMWG;
-  c.nsplit = choose_nsplit(p);
+  const AttnPlan plan = plan_attn(p);
+  c.MB = (c.M + plan.mwg - 1) / plan.mwg;
+  c.nsplit = plan.nsplit;
   c.n_groups = p->B * p->Hkv * c.nsplit;
   c.c = p->sm_scale * kLog2e;
   c.q = (const uint16_t*)p->q; c.ks = (const uint16_t*)p->k_shared; c.vs = (const uint16_t*)p->v_shared;
@@ -532,7 +537,6 @@ extern "C" gr_status gr_beam_attn(const gr_attn_params* p, void* workspace, size
   const int64_t groups_padded = ((int64_t)c.n_groups + 7) / 8 * 8;
   const int64_t grid = groups_padded * c.MB;
   if (grid >= ((int64_t)1 << 31)) return GR_ERR_UNSUPPORTED;
-  const int var = attn_variant();
   const size_t lds = (size_t)2 * KT * ((p->d + 8) + (p->d + 16)) * 2;
 #define GR_LAUNCH_ATTN(DD, NCB_, NW_)                                                                                        \
   do {                                                                                                                       \
@@ -540,9 +544,9 @@ extern "C" gr_status gr_beam_attn(const gr_attn_params* p, void* workspace, size
     hipLaunchKernelGGL((k_beam_attn<DD, NCB_, NW_>), dim3((unsigned)grid), dim3(NW_ * 64), lds, stream, c);                  \
   } while (0)
   if (p->d == 128) {
-    if (var == 1) GR_LAUNCH_ATTN(128, 1, 8); else if (var == 2) GR_LAUNCH_ATTN(128, 1, 4); else GR_LAUNCH_ATTN(128, 2, 4);
+    if (plan.mwg == 256) GR_LAUNCH_ATTN(128, 1, 8); else GR_LAUNCH_ATTN(128, 1, 4);
   } else {
-    if (var == 1) GR_LAUNCH_ATTN(64, 1, 8); else if (var == 2) GR_LAUNCH_ATTN(64, 1, 4); else GR_LAUNCH_ATTN(64, 2, 4);
+    if (plan.mwg == 256) GR_LAUNCH_ATTN(64, 1, 8); else GR_LAUNCH_ATTN(64, 1, 4);
   }
 #undef GR_LAUNCH_ATTN
   if (c.nsplit > 1) {
