@@ -317,17 +317,22 @@ k_beam_attn(AttnCtx c) {
 
     f32x16 s_a[KT / 32][NCB], s_b[KT / 32][NCB];      // ping-pong score accumulators: no copies
     T::qk(s_k, qop, s_a, n32, G);
+    // ntiles - 1 steps, then the last tile.  An odd step is peeled off first so that the loop runs
+    // whole ping-pong pairs and the last tile is always in s_a.
     int t = 0;
-    for (; t + 2 < ntiles; t += 2) {
+    if ((ntiles - 1) & 1) {
+      step(s_a, s_b, 0);
+#pragma unroll
+      for (int sub = 0; sub < KT / 32; sub++)
+#pragma unroll
+        for (int cb = 0; cb < NCB; cb++) s_a[sub][cb] = s_b[sub][cb];
+      t = 1;
+    }
+    for (; t + 1 < ntiles; t += 2) {
       step(s_a, s_b, t);
       step(s_b, s_a, t + 1);
     }
-    if (t + 1 < ntiles) {
-      step(s_a, s_b, t);
-      last(s_b, t + 1);
-    } else {
-      last(s_a, t);
-    }
+    last(s_a, t);
   }
 
   // ---- epilogue: unshared stage + merge (segment 0), then normalise or write partials
@@ -341,7 +346,7 @@ k_beam_attn(AttnCtx c) {
     if (sp == 0) {
       // unshared stage: this beam's own u decode tokens, up to UCH at a time so that all of their
       // K rows (then all of their V rows) are in flight together instead of one latency per token
-      constexpr int UCH = 4;
+      constexpr int UCH = 2;
       for (int j0 = 0; j0 < c.u; j0 += UCH) {
         const size_t off0 = ((((size_t)b * c.W + w) * c.ND + j0) * c.Hkv + kvh) * D;
         const size_t jstride = (size_t)c.Hkv * D;

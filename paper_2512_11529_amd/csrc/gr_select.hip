@@ -116,6 +116,24 @@ __device__ __forceinline__ int lower_bound_i32(const int32_t* a, int n, int key)
   return lo;
 }
 
+// exp(y) for y <= 0 in fp64, about 2 ulp: y = (64 n' + j) ln2/64 + r with |r| <= ln2/128,
+// exp(y) = 2^n' * 2^(j/64) * (1 + r + r^2/2 + ... + r^5/120).  `tab` holds 2^(j/64), j = 0..63.
+// Far cheaper than a general-purpose exp; its error is ~1e-16 relative, which the fp64 sum of a
+// row carries unchanged into the single fp32 rounding of lse.
+__device__ __forceinline__ double exp_nonpos(double y, const double* tab) {
+  const double nf = rint(y * 92.33248261689366);              // 64 / ln 2
+  double r = fma(nf, -0x1.62e42fee00000p-7, y);                // ln2/64, high 32 bits (exact product)
+  r = fma(nf, -0x1.a39ef35793c76p-39, r);                      // ln2/64, low part
+  double p = fma(r, 1.0 / 120.0, 1.0 / 24.0);
+  p = fma(p, r, 1.0 / 6.0);
+  p = fma(p, r, 0.5);
+  p = fma(p, r, 1.0);
+  p = p * r;
+  const int n = (int)nf;
+  const double t = tab[n & 63];
+  return ldexp(fma(t, p, t), n >> 6);
+}
+
 template <int NWAVES>
 __device__ __forceinline__ float block_max(float v, float* s_red) {
   v = gr_wave_max(v);
@@ -159,6 +177,7 @@ __global__ void __launch_bounds__(kRowThreads) k_row_dense(SelCtx c, int owns_de
   __shared__ double s_redd[kRowThreads / 64];
   __shared__ uint32_t s_redu[kRowThreads / 64];
   __shared__ float s_bias;
+  __shared__ double s_tab[64];
   const int row = blockIdx.x;
   const int tid = threadIdx.x;
   const float s_in = c.scores_in[row];
@@ -180,6 +199,7 @@ __global__ void __launch_bounds__(kRowThreads) k_row_dense(SelCtx c, int owns_de
       if (row_is_sparse(c, n_list)) return;      // k_row_sparse owns this row
     }
   }
+  if (tid < 64) s_tab[tid] = exp2((double)tid * (1.0 / 64.0));
   // ---- validity bits of the row in LDS
   const int words = (V + 31) >> 5;
   if (!c.blob) {
@@ -233,10 +253,10 @@ __global__ void __launch_bounds__(kRowThreads) k_row_dense(SelCtx c, int owns_de
       const double md = (double)m;
 #pragma unroll
       for (int i = 0; i < kRegV4; i++) {
-        if (vb[i] & 1u) S += exp((double)xr[i].x - md);
-        if (vb[i] & 2u) S += exp((double)xr[i].y - md);
-        if (vb[i] & 4u) S += exp((double)xr[i].z - md);
-        if (vb[i] & 8u) S += exp((double)xr[i].w - md);
+        if (vb[i] & 1u) S += exp_nonpos((double)xr[i].x - md, s_tab);
+        if (vb[i] & 2u) S += exp_nonpos((double)xr[i].y - md, s_tab);
+        if (vb[i] & 4u) S += exp_nonpos((double)xr[i].z - md, s_tab);
+        if (vb[i] & 8u) S += exp_nonpos((double)xr[i].w - md, s_tab);
       }
     }
   } else {
@@ -251,7 +271,7 @@ __global__ void __launch_bounds__(kRowThreads) k_row_dense(SelCtx c, int owns_de
       const double md = (double)m;
       for (int e = 0; e < epc; e++) {
         const int v = dense_slot_token(c, tid, e);
-        if (v < V && ((s_mask[v >> 5] >> (v & 31)) & 1u)) S += exp((double)x[v] - md);
+        if (v < V && ((s_mask[v >> 5] >> (v & 31)) & 1u)) S += exp_nonpos((double)x[v] - md, s_tab);
       }
     }
   }
@@ -279,6 +299,9 @@ __global__ void __launch_bounds__(kRowThreads) k_row_dense(SelCtx c, int owns_de
 // sparse form).  Chunk k of such a row = children k, k+64, k+128, ...
 // ------------------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(kRowThreads) k_row_sparse(SelCtx c) {
+  __shared__ double s_tab[64];
+  if (threadIdx.x < 64) s_tab[threadIdx.x] = exp2((double)threadIdx.x * (1.0 / 64.0));
+  __syncthreads();
   const int row = blockIdx.x * (kRowThreads / 64) + (threadIdx.x >> 6);
   const int lane = threadIdx.x & 63;
   if (row >= c.B * c.W) return;
@@ -314,7 +337,7 @@ __global__ void __launch_bounds__(kRowThreads) k_row_sparse(SelCtx c) {
   const double md = (double)m;
 #pragma unroll
   for (int k = 0; k < kSparseMax / 64; k++)
-    if (lane + 64 * k < n) S += exp((double)xv[k] - md);
+    if (lane + 64 * k < n) S += exp_nonpos((double)xv[k] - md, s_tab);
   S = gr_wave_sum(S);
   const float lse = (float)((double)m + log(S));
   const float bias = __fsub_rn(s_in, lse);
