@@ -22,6 +22,20 @@ PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
 
 
+def _stored_traffic(config_id):
+    """HBM bytes per attention launch measured with rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE, scaled by a plain
+    copy of known size); the figures and the commands that produced them are in profiles/attn_hbm_traffic.txt."""
+    path = os.path.join(ROOT, "profiles", "attn_hbm_traffic.txt")
+    try:
+        for line in open(path):
+            parts = line.split()
+            if len(parts) >= 3 and parts[0] == "traffic_bytes_per_launch" and parts[1] == f"config{config_id}":
+                return float(parts[2])
+    except OSError:
+        pass
+    return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -32,6 +46,9 @@ def main():
     ap.add_argument("--cpu-sample-requests", type=int, default=0, help="requests timed on the CPU oracle (0 = auto)")
     ap.add_argument("--flags", type=int, default=0, help="GR_SELECT_* flags for the item step")
     ap.add_argument("--no-mask", action="store_true", help="unconstrained item step (mask = NULL)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy (known HBM traffic) so that rocprofv3 FETCH_SIZE / WRITE_SIZE "
+                         "readings of the same run can be scaled")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; requests shard across GPUs with no exchange (see DESIGN.md), "
@@ -103,6 +120,13 @@ def main():
     torch.cuda.synchronize()
     live_rows = [int((state[s]["scores"] > float("-inf")).sum().item()) for s in range(ND)]
 
+    if args.calibrate_copy:
+        src = torch.zeros(1 << 28, dtype=torch.float32, device=dev)      # 1 GiB
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     # ---------------- warm-up, then K timed steps
     for i in range(args.warmup):
         attn(i % ND); select(i % ND)
@@ -136,7 +160,7 @@ def main():
     attn_ms_avg = float(np.mean(attn_ms))
     attn_tflops = attn_flops_avg / (attn_ms_avg * 1e-3) / 1e12
     roofline = dict(bound="mfma", kernel="k_beam_attn", achieved=round(attn_tflops, 2), peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
-                    frac=round(attn_tflops / PEAK_BF16_TFLOPS, 4), traffic=None,
+                    frac=round(attn_tflops / PEAK_BF16_TFLOPS, 4), traffic=_stored_traffic(cfg.config_id),
                     avg_launch_ms=round(attn_ms_avg, 4), flops_per_launch=attn_flops_avg)
     # item step: algorithmic bytes of a dense pass = live rows * (4V logits + V/8 mask bits)
     sel_by_level = {}
