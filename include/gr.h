@@ -6,7 +6,8 @@
  *      the prompt K/V per request plus W short per-beam decode caches (Sections 5.1, 5.2);
  *   2. the beam item step: valid-item mask, log-softmax over valid tokens, cumulative beam score,
  *      and the best W of the W*V candidates (Sections 6.1, 6.2), in fixed caller-owned buffers
- *      (Section 6.3).
+ *      (Section 6.3);
+ *   3. the move of every surviving beam's own decode cache to its new slot, in place (Section 5.1).
  *
  * Conventions for every entry point
  *   - All data pointers are DEVICE pointers unless a comment says "host".  Parameter structs and
@@ -157,6 +158,25 @@ size_t gr_beam_select_workspace_bytes(int32_t B, int32_t W, int32_t V, int32_t d
 /* Enqueue the item step.  `workspace`: device, 256-byte aligned, contents unspecified before and
  * after.  Errors: INVALID_ARG, UNSUPPORTED, WORKSPACE_TOO_SMALL, HIP. */
 gr_status gr_beam_select(const gr_select_params* p, void* workspace, size_t workspace_bytes, void* stream);
+
+/* ------------------------------------------------------------------------------------------------
+ * gr_beam_reorder - in-place update of the unshared cache between two decode steps (Section 5.1).
+ *
+ * After gr_beam_select, slot j of the new beam generation continues old beam parent[b, j].  The
+ * per-beam decode cache follows it inside the single buffer that holds it (no second copy):
+ *     cache[b, j, t, :, :] <- cache[b, parent[b, j], t, :, :]     for token slots t in [0, u)
+ * for both K and V.  Slots with parent < 0 (dead beams) are zero-filled; token slots >= u are left
+ * untouched (the caller writes slot u next).  The paper orders row moves by direction so that no
+ * block is overwritten before it is read; this call gives the same guarantee for any parent
+ * array (unsorted, repeated parents) by gathering before a barrier and writing after it.
+ *
+ * parent: device int32 [B, W] (gr_beam_select's parent_out).  k_unshared, v_unshared: device bf16
+ * [B, W, ND, Hkv, d], 16-byte aligned, distinct buffers, modified in place.  Only enqueues on
+ * `stream`.  Supported: W <= 2048; B <= 65535; Hkv*d a multiple of 8.  Errors: INVALID_ARG,
+ * UNSUPPORTED, HIP.
+ * ------------------------------------------------------------------------------------------------ */
+gr_status gr_beam_reorder(int32_t B, int32_t W, int32_t ND, int32_t Hkv, int32_t d, int32_t u,
+                          const int32_t* parent, void* k_unshared, void* v_unshared, void* stream);
 
 #ifdef __cplusplus
 }

@@ -1,10 +1,11 @@
 """MI355X (gfx950) hot path of a generative-recommendation decode step: thin binding over libgr.so.
 
-The three calls have the names and meaning of the C ABI in include/gr.h:
+The calls have the names and meaning of the C ABI in include/gr.h:
 
     gr_beam_attn         shared-prefix beam attention over a separated KV cache
     gr_item_mask_build   valid-item mask blob from the sorted item table (load time)
     gr_beam_select       masked log-softmax + beam score accumulation + top-W selection
+    gr_beam_reorder      in-place move of the surviving beams' own KV cache to their new slots
 
 This module only marshals arguments (torch CUDA tensors -> device pointers, current stream ->
 hipStream_t).  Every step of the path runs in the HIP kernels; there is no CPU or PyTorch fallback,
@@ -15,7 +16,7 @@ import os
 
 from . import build as _build
 
-__all__ = ["load_library", "gr_beam_attn", "gr_item_mask_build", "gr_beam_select", "gr_status_string",
+__all__ = ["load_library", "gr_beam_attn", "gr_item_mask_build", "gr_beam_select", "gr_beam_reorder", "gr_status_string",
            "attn_workspace_bytes", "select_workspace_bytes", "GrError", "GR_SELECT_FORCE_DENSE", "LIB_PATH"]
 
 LIB_PATH = _build.LIB_PATH
@@ -73,6 +74,8 @@ def load_library(path: str = None):
     lib.gr_beam_select_workspace_bytes.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32]
     lib.gr_beam_select.restype = ctypes.c_int32
     lib.gr_beam_select.argtypes = [ctypes.POINTER(_SelectParams), ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+    lib.gr_beam_reorder.restype = ctypes.c_int32
+    lib.gr_beam_reorder.argtypes = [ctypes.c_int32] * 6 + [ctypes.c_void_p] * 4
     _lib = lib
     return lib
 
@@ -209,3 +212,17 @@ def gr_beam_select(mask, logits, scores_in, prefix_in, range_in, step, flags=0, 
     if rc != 0:
         raise GrError(rc, "gr_beam_select")
     return out
+
+
+def gr_beam_reorder(parent, k_unshared, v_unshared, u, stream=None):
+    """Move every surviving beam's own KV cache to its new slot, in place.  parent int32 [B,W] (from
+    gr_beam_select); k/v_unshared bf16 [B,W,ND,Hkv,d]; token slots [0,u) move.  Enqueues on `stream`."""
+    import torch
+    lib = load_library()
+    B, W, ND, Hkv, d = k_unshared.shape
+    _check(parent, torch.int32, (B, W), "parent")
+    _check(k_unshared, torch.bfloat16, None, "k_unshared")
+    _check(v_unshared, torch.bfloat16, tuple(k_unshared.shape), "v_unshared")
+    rc = lib.gr_beam_reorder(B, W, ND, Hkv, d, int(u), _ptr(parent), _ptr(k_unshared), _ptr(v_unshared), _stream(stream))
+    if rc != 0:
+        raise GrError(rc, "gr_beam_reorder")

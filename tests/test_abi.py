@@ -54,6 +54,8 @@ def test_null_and_range_arguments_are_rejected_on_the_host(gr):
     assert lib.gr_beam_attn(None, None, 0, None) == -1
     assert lib.gr_beam_select(None, None, 0, None) == -1
     assert lib.gr_item_mask_build(None, 10, 3, 8, None, 0, None, 0, None) == -1
+    assert lib.gr_beam_reorder(1, 4, 3, 2, 64, 1, None, None, None, None) == -1      # null pointers
+    assert lib.gr_beam_reorder(1, 4, 3, 2, 64, 4, None, None, None, None) == -1      # u > ND
     p = gr._SelectParams()
     p.B, p.W, p.V, p.depth, p.step = 1, 4, 8, 3, 5
     assert lib.gr_beam_select(ctypes.byref(p), None, 0, None) == -1
