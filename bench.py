@@ -46,6 +46,8 @@ def main():
     ap.add_argument("--cpu-sample-requests", type=int, default=0, help="requests timed on the CPU oracle (0 = auto)")
     ap.add_argument("--flags", type=int, default=0, help="GR_SELECT_* flags for the item step")
     ap.add_argument("--no-mask", action="store_true", help="unconstrained item step (mask = NULL)")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the untimed extras reported beside the headline (cache reorder timing, whole-step HIP graph replay)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (known HBM traffic) so that rocprofv3 FETCH_SIZE / WRITE_SIZE "
                          "readings of the same run can be scaled")
@@ -171,6 +173,57 @@ def main():
             sel_by_level[f"level{s}"] = dict(ms=round(float(np.mean(ms)), 4), live_rows=live_rows[s],
                                              dense_GBps=round(dense_bytes / (float(np.mean(ms)) * 1e-3) / 1e9, 1))
 
+    # ---------------- extras, outside the headline's timed region
+    reorder, graph = None, None
+    if not args.no_extras:
+        # (1) in-place move of the surviving beams' decode cache (gr_beam_reorder) with the parents each level selected
+        ku_w, vu_w = attn_in[ND - 1]["ku"].clone(), attn_in[ND - 1]["vu"].clone()
+        reorder = {}
+        for s in range(ND):
+            par = sel_out[s]["parent"]
+            for _ in range(2):
+                gr.gr_beam_reorder(par, ku_w, vu_w, s + 1)
+            r0, r1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            reps = 10
+            r0.record()
+            for _ in range(reps):
+                gr.gr_beam_reorder(par, ku_w, vu_w, s + 1)
+            r1.record()
+            torch.cuda.synchronize()
+            ms = r0.elapsed_time(r1) / reps
+            moved = 2.0 * 2.0 * B * W * (s + 1) * Hkv * d * 2          # K and V, read + write
+            reorder[f"u{s + 1}"] = dict(ms=round(ms, 4), GBps=round(moved / (ms * 1e-3) / 1e9, 1))
+        del ku_w, vu_w
+        # (2) the ND-level cycle (attention + item step per level) captured once as a HIP graph and replayed
+        try:
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(side):
+                for s in range(ND):
+                    attn(s); select(s)
+            torch.cuda.current_stream().wait_stream(side)
+            torch.cuda.synchronize()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                for s in range(ND):
+                    attn(s); select(s)
+            for _ in range(2):
+                g.replay()
+            torch.cuda.synchronize()
+            ref = {k: sel_out[ND - 1][k].clone() for k in ("parent", "token", "scores")}
+            cycles = max(1, K // ND)
+            g0, g1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            g0.record()
+            for _ in range(cycles):
+                g.replay()
+            g1.record()
+            torch.cuda.synchronize()
+            gms = g0.elapsed_time(g1) / (cycles * ND)
+            same = all(bool(torch.equal(ref[k], sel_out[ND - 1][k])) for k in ref)
+            graph = dict(ms_per_step=round(gms, 4), steps_per_s=round(1000.0 / gms, 3), cycles=cycles, replay_matches_eager=same)
+        except Exception as e:          # the headline above stands on its own
+            graph = dict(error=f"{type(e).__name__}: {e}"[:300])
+
     # ---------------- CPU oracle on a bounded sample of the same workload
     cpu = None
     if not args.no_cpu_baseline:
@@ -205,7 +258,7 @@ def main():
         roofline=roofline, cpu_baseline=cpu,
         attn=dict(ms_by_u={f"u{s + 1}": round(float(np.mean([attn_ms[i] for i in range(K) if i % ND == s] or [0])), 4) for s in range(ND)},
                   tflops=round(attn_tflops, 2)),
-        select=sel_by_level, wall_s=round(wall, 3), input_gen_s=round(t_gen, 1))
+        select=sel_by_level, reorder=reorder, graph=graph, wall_s=round(wall, 3), input_gen_s=round(t_gen, 1))
     print(json.dumps(line))
 
 

@@ -1,0 +1,71 @@
+"""GPU: one decode step (attention -> item step -> cache reorder) captured as a HIP graph replays to
+the eager results.  The entry points only enqueue kernels on the caller's stream (no allocation, no
+synchronisation, no memset nodes), which is what makes the step capturable as a whole."""
+import numpy as np
+import pytest
+
+import gr_synth
+from gpu_util import bf16_to_dev, to_dev
+
+pytestmark = pytest.mark.gpu
+
+
+def test_step_graph_replays_match_eager():
+    import torch
+    import paper_2512_11529_amd as gr
+    gr.load_library()
+    cfg = gr_synth.get_config(1)
+    B, W, ND, Hq, Hkv, d, V = cfg.B, cfg.W, cfg.ND, cfg.Hq, cfg.Hkv, cfg.d, cfg.V
+    dev = torch.device("cuda:0")
+    items = gr_synth.make_item_table(cfg)
+    mask = gr.gr_item_mask_build(to_dev(items), V)
+    a = gr_synth.make_attention_inputs(cfg, 1)
+    cu = a["cu_seqlens"]
+    q, ks, vs = bf16_to_dev(a["q"]), bf16_to_dev(a["k_shared"]), bf16_to_dev(a["v_shared"])
+    ku0, vu0 = bf16_to_dev(a["k_unshared"]), bf16_to_dev(a["v_unshared"])
+    ku, vu = ku0.clone(), vu0.clone()
+    d_cu = to_dev(cu)
+    scale = float(np.float32(1 / np.sqrt(d)))
+    max_L, total_L = int(np.diff(cu).max()), int(cu[-1])
+    out = torch.empty_like(q)
+    ws_attn = torch.empty(max(gr.attn_workspace_bytes(B, W, Hq, Hkv, d, max_L), 256), dtype=torch.uint8, device=dev)
+    ws_sel = torch.empty(gr.select_workspace_bytes(B, W, V, ND), dtype=torch.uint8, device=dev)
+    sc, pf, rg = gr_synth.initial_beam_state(B, W, ND)
+    # a level-1 state to select from: run level 0 eagerly first
+    logits0, logits1 = to_dev(gr_synth.make_logits(cfg, 0)), to_dev(gr_synth.make_logits(cfg, 1))
+    st0 = gr.gr_beam_select(mask, logits0, to_dev(sc), to_dev(pf), to_dev(rg), 0)
+    sel = {k: torch.empty_like(v) for k, v in st0.items()}
+
+    def step():
+        gr.gr_beam_attn(q, ks, vs, d_cu, ku, vu, 2, scale, max_L, total_L, out=out, workspace=ws_attn)
+        gr.gr_beam_select(mask, logits1, st0["scores"], st0["prefix"], st0["range"], 1, out=sel, workspace=ws_sel)
+        gr.gr_beam_reorder(sel["parent"], ku, vu, 2)
+
+    step()
+    torch.cuda.synchronize()
+    want = dict(out=out.clone(), ku=ku.clone(), vu=vu.clone(), **{k: v.clone() for k, v in sel.items()})
+
+    def reset():
+        ku.copy_(ku0); vu.copy_(vu0); out.zero_()
+        for v in sel.values():
+            v.zero_()
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        reset(); step()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    reset()
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        step()
+    for rep in range(3):
+        reset()                                  # eager work and a synchronisation between replays
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        got = dict(out=out, ku=ku, vu=vu, **sel)
+        for k in want:
+            assert torch.equal(got[k], want[k]), f"replay {rep}: {k} differs from the eager step"
