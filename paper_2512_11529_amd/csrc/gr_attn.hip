@@ -21,6 +21,7 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int KT = 64;        // kv tokens per LDS tile
 constexpr float kLog2e = 1.4426950408889634f;
@@ -230,28 +231,34 @@ k_beam_attn(AttnCtx c) {
   for (int cb = 0; cb < NCB; cb++) { m_run[cb] = -INFINITY; l_run[cb] = 0.f; }
 
   // ---- K/V tile staging: global -> registers (one tile ahead) -> LDS
-  const uint16_t* kbase = c.ks + ((size_t)row0 * c.Hkv + kvh) * D;
-  const uint16_t* vbase = c.vs + ((size_t)row0 * c.Hkv + kvh) * D;
-  const int tok_stride = c.Hkv * D;                       // elements between consecutive tokens
+  // Tiles are fetched with buffer loads: the descriptor (scalar registers) is rebuilt per tile from
+  // the tile's first row and the bytes left in the segment, the per-thread offsets never change, and
+  // rows past the end of the segment come back as zeros from the hardware range check (the -inf
+  // score mask on the K side and zero probabilities on the V side make them irrelevant).
+  const uint32_t tok_bytes = (uint32_t)c.Hkv * D * 2;       // bytes between consecutive tokens
+  const char* kbase = (const char*)c.ks + ((size_t)row0 * c.Hkv + kvh) * D * 2;
+  const char* vbase = (const char*)c.vs + ((size_t)row0 * c.Hkv + kvh) * D * 2;
   struct Stage { uint4 r[PPT]; };
   Stage kreg, vreg;
-  int prow[PPT], pcol[PPT];                               // this thread's 16-byte pieces of a tile (loop invariant)
-#pragma unroll
-  for (int i = 0; i < PPT; i++) { const int p = tid + i * NT; prow[i] = p / PPR; pcol[i] = (p % PPR) * 8; }
-  // Rows past the end of the segment re-read its last row: finite data that the -inf score mask
-  // (K side) and the zero probabilities (V side) make irrelevant, and no branch in the load path.
-  auto gload = [&](const uint16_t* base, int t) {
-    const int tok0 = seg0 + t * KT;
-    const int last = seg1 - tok0 - 1;
-    const uint16_t* tile = base + (size_t)tok0 * tok_stride;   // wave-uniform
+  constexpr int RPI = NT / PPR;                              // piece i of a thread sits RPI rows below piece i-1
+  const int prow0 = tid / PPR, pcol0 = (tid % PPR) * 8;
+  const uint32_t voff0 = (uint32_t)prow0 * tok_bytes + (uint32_t)pcol0 * 2;
+  auto gload = [&](const char* base, int t) {
+    const int tok0 = seg0 + t * KT;                                          // wave-uniform
+    const char* tile = base + (size_t)tok0 * tok_bytes;
+    const uint32_t left = (uint32_t)(seg1 - tok0 - 1) * tok_bytes + D * 2;   // up to the end of the last valid row
+    const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)tile, 0, left, 0x00020000);
     Stage st;
 #pragma unroll
-    for (int i = 0; i < PPT; i++) st.r[i] = *(const uint4*)(tile + min(prow[i], last) * tok_stride + pcol[i]);
+    for (int i = 0; i < PPT; i++) {
+      const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rsrc, voff0 + (uint32_t)(i * RPI) * tok_bytes, 0, 0);
+      st.r[i] = make_uint4(v.x, v.y, v.z, v.w);
+    }
     return st;
   };
   auto lstore = [&](uint16_t* dst, int stride, const Stage& st) {
 #pragma unroll
-    for (int i = 0; i < PPT; i++) *(uint4*)(&dst[prow[i] * stride + pcol[i]]) = st.r[i];
+    for (int i = 0; i < PPT; i++) *(uint4*)(&dst[(prow0 + i * RPI) * stride + pcol0]) = st.r[i];
   };
 
   if (ntiles > 0) {
@@ -516,6 +523,7 @@ extern "C" gr_status gr_beam_attn(const gr_attn_params* p, void* workspace, size
   if (p->Hq % p->Hkv) return GR_ERR_INVALID_ARG;
   if (p->d != 64 && p->d != 128) return GR_ERR_UNSUPPORTED;
   if (p->total_L >= ((int64_t)1 << 31)) return GR_ERR_UNSUPPORTED;
+  if ((int64_t)p->max_L * p->Hkv * p->d * 2 >= ((int64_t)1 << 32)) return GR_ERR_UNSUPPORTED;   // one request's K (or V) must fit a buffer descriptor
   const int g = p->Hq / p->Hkv;
   if ((int64_t)p->W * g >= ((int64_t)1 << 30)) return GR_ERR_UNSUPPORTED;
 
