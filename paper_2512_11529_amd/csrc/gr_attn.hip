@@ -261,6 +261,50 @@ k_beam_attn(AttnCtx c) {
     for (int i = 0; i < PPT; i++) *(uint4*)(&dst[(prow0 + i * RPI) * stride + pcol0]) = st.r[i];
   };
 
+  // ---- geometry of the unshared stage (segment 0 only): every beam's own u decode tokens go through
+  // the same MFMA path as the prompt.  The 32 query columns of a wave belong to a handful of beams
+  // (32/g of them when g divides 32).  Their K rows (then V rows) form private 32-row mini-tiles,
+  // row rho = beam_local * u + token, loaded with coalesced 16-byte pieces into the wave's own slice
+  // of the (by then idle) tile memory; S^T = K_u . Q^T is a full 32 x 32 block of which a column
+  // keeps only its own beam's u rows (the rest are masked to -inf), and O^T += V_u^T . P^T follows.
+  // Compared with per-lane dot products this reads each beam's rows once instead of once per query
+  // head and replaces ~1000 VALU operations per lane by 16 MFMAs per wave.  The first mini-tile is
+  // fetched into registers while the last prompt tile is still being processed.
+  static_assert(NCB == 1, "one column block per wave");
+  constexpr int UR = 32;                                 // rows of a mini-tile
+  constexpr int UP = UR * PPR / 64;                      // 16-byte pieces per lane and tensor
+  const bool own_stage = sp == 0 && c.u > 0;
+  auto wave_rows = [&](int wv, int* first_beam) {        // rows of wave wv's mini-tiles, and its first beam
+    const int r_first = mbi * MWG + wv * 32;
+    if (r_first >= c.M) { *first_beam = 0; return 0; }
+    const int r_last = min(r_first + 31, c.M - 1);
+    *first_beam = r_first / c.g;
+    return (r_last / c.g - *first_beam + 1) * c.u;
+  };
+  int beam0 = 0, npass = 0, R = 0;
+  if (own_stage) {
+    for (int wv = 0; wv < NWAVES; wv++) { int fb; npass = max(npass, (wave_rows(wv, &fb) + UR - 1) / UR); }
+    R = wave_rows(wave, &beam0);
+  }
+  const int my_lo = (qrow[0] >= 0) ? (qrow[0] / c.g - beam0) * c.u : -1;         // this column's rows [my_lo, my_lo + u)
+  uint4 ukp[UP], uvp[UP];
+  auto uload = [&](int pass) {                           // 32 rows x D/8 pieces per tensor; a row = PPR consecutive lanes
+    const size_t tok_elems = (size_t)c.Hkv * D;
+#pragma unroll
+    for (int i = 0; i < UP; i++) {
+      const int pi = lane + 64 * i, row = pi / PPR, col = (pi % PPR) * 8;
+      const int rho = pass * UR + row;
+      ukp[i] = make_uint4(0, 0, 0, 0);
+      uvp[i] = make_uint4(0, 0, 0, 0);
+      if (rho < R) {
+        const int bl = rho / c.u, tok = rho - bl * c.u;
+        const size_t off = (((size_t)b * c.W + beam0 + bl) * c.ND + tok) * tok_elems + (size_t)kvh * D + col;
+        ukp[i] = *(const uint4*)(c.ku + off);
+        uvp[i] = *(const uint4*)(c.vu + off);
+      }
+    }
+  };
+
   if (ntiles > 0) {
     // Pipeline: iteration t issues S(t+1) = K(t+1).Q^T together with the softmax of S(t), then O += V(t).P(t).
     // K(t+2) and V(t+1) are written to LDS right after the barrier that opens iteration t, so one
@@ -302,6 +346,7 @@ k_beam_attn(AttnCtx c) {
     };
     // the last tile of the segment: the only one that can be partial, and it has no successor
     auto last = [&](f32x16 (&s_in)[KT / 32][NCB], int t) {
+      if (own_stage) uload(0);
       __syncthreads();
       const int tok0 = seg0 + t * KT;
       if (tok0 + KT > seg1) {
@@ -342,75 +387,96 @@ k_beam_attn(AttnCtx c) {
     last(s_a, t);
   }
 
-  // ---- epilogue: unshared stage + merge (segment 0), then normalise or write partials
+  // ---- unshared stage (segment 0): every beam's own u decode tokens, through the same MFMA path.
+  // The 32 query columns of a wave belong to a handful of beams (32/g of them when g divides 32).
+  // Their K rows (then V rows) are laid out as private 32-row mini-tiles, row rho = beam_local * u +
+  // token, loaded with coalesced 16-byte pieces into the wave's own slice of the (now idle) tile
+  // memory; S^T = K_u . Q^T is a full 32 x 32 block of which a column keeps only its own beam's u
+  // rows (the rest are masked to -inf), and O^T += V_u^T . P^T follows.  Compared with per-lane dot
+  // products this reads each beam's rows once instead of once per query head and replaces ~1000
+  // VALU operations per lane by 16 MFMAs per wave.
+  if (own_stage) {
+    float m = m_run[0], l = l_run[0];
+    __syncthreads();                                       // every wave is done with the prompt tiles
+    uint16_t* s_uk = smem + wave * UR * KSTR;
+    uint16_t* s_uv = smem + NWAVES * UR * KSTR + wave * UR * VSTR;
+    if (ntiles == 0) uload(0);
+    for (int pass = 0; pass < npass; pass++) {
+      if (pass > 0) uload(pass);
+#pragma unroll
+      for (int i = 0; i < UP; i++) {
+        const int pi = lane + 64 * i, row = pi / PPR, col = (pi % PPR) * 8;
+        *(uint4*)(&s_uk[row * KSTR + col]) = ukp[i];
+        *(uint4*)(&s_uv[row * VSTR + col]) = uvp[i];
+      }
+      __syncthreads();
+      // scores of the 32 rows against the wave's 32 columns
+      f32x16 su;
+#pragma unroll
+      for (int i = 0; i < 16; i++) su[i] = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < D / 16; ks++) {
+        const bf16x8 a = as_bf16x8(*(const uint4*)(&s_uk[n32 * KSTR + ks * 16 + G * 8]));
+        su = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qop[0][ks], su, 0, 0, 0);
+      }
+      // keep the column's own rows; online-softmax update of (m, l, O)
+      float mx = -INFINITY;
+      bool mine[16];
+#pragma unroll
+      for (int i = 0; i < 16; i++) {
+        const int rho = pass * UR + 8 * (i / 4) + 4 * G + (i % 4);
+        mine[i] = my_lo >= 0 && rho >= my_lo && rho < my_lo + c.u;
+        if (mine[i]) mx = fmaxf(mx, su[i]);
+      }
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      const float m_new = fmaxf(m, mx);
+      const bool any_key = m_new > -INFINITY;              // false only while the column has seen no key at all
+      const float alpha = any_key ? __builtin_amdgcn_exp2f((m - m_new) * c.c) : 1.f;
+      float rs = 0.f;
+#pragma unroll
+      for (int i = 0; i < 16; i++) {
+        const float pr = mine[i] ? __builtin_amdgcn_exp2f((su[i] - m_new) * c.c) : 0.f;
+        su[i] = pr;
+        rs += pr;
+      }
+      l = l * alpha + rs;
+      m = m_new;
+#pragma unroll
+      for (int db = 0; db < D / 32; db++)
+#pragma unroll
+        for (int i = 0; i < 16; i++) o_acc[db][0][i] *= alpha;
+      bf16x8 pu[UR / 16];
+#pragma unroll
+      for (int t = 0; t < UR / 16; t++)
+#pragma unroll
+        for (int e = 0; e < 8; e++) pu[t][e] = (__bf16)su[8 * t + e];
+      {
+        typedef short s16x8 __attribute__((ext_vector_type(8)));
+        const uint16_t* vb = s_uv + (4 * G + ((lane & 15) >> 2)) * VSTR + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+#pragma unroll
+        for (int t = 0; t < UR / 16; t++)
+#pragma unroll
+          for (int db = 0; db < D / 32; db++) {
+            const uint16_t* p0 = vb + t * 16 * VSTR + db * 32;
+            s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p0));
+            s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p0 + 8 * VSTR));
+            s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+            o_acc[db][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both), pu[t], o_acc[db][0], 0, 0, 0);
+          }
+      }
+      if (pass + 1 < npass) __syncthreads();               // the mini-tiles are rewritten by the next pass
+    }
+    m_run[0] = m; l_run[0] = l;
+  }
+
+  // ---- epilogue: merge is already done in registers; normalise or write this segment's partials
 #pragma unroll
   for (int cb = 0; cb < NCB; cb++) {
     const int r = qrow[cb];
     if (r < 0) continue;
     const int w = r / c.g, j = r % c.g;
     const int hq = kvh * c.g + j;
-    float m = m_run[cb], l = l_run[cb];
-    if (sp == 0) {
-      // unshared stage: this beam's own u decode tokens, up to UCH at a time so that all of their
-      // K rows (then all of their V rows) are in flight together instead of one latency per token
-      constexpr int UCH = 2;
-      for (int j0 = 0; j0 < c.u; j0 += UCH) {
-        const size_t off0 = ((((size_t)b * c.W + w) * c.ND + j0) * c.Hkv + kvh) * D;
-        const size_t jstride = (size_t)c.Hkv * D;
-        float dot[UCH];
-#pragma unroll
-        for (int jj = 0; jj < UCH; jj++) {
-          dot[jj] = -INFINITY;
-          if (j0 + jj < c.u) {
-            const uint16_t* kp = c.ku + off0 + jj * jstride + G * 8;
-            uint4 kv[D / 16];
-#pragma unroll
-            for (int ks = 0; ks < D / 16; ks++) kv[ks] = *(const uint4*)(kp + ks * 16);
-            float acc = 0.f;
-#pragma unroll
-            for (int ks = 0; ks < D / 16; ks++) {
-              const uint32_t kw[4] = {kv[ks].x, kv[ks].y, kv[ks].z, kv[ks].w};
-#pragma unroll
-              for (int e = 0; e < 4; e++) {
-                acc = fmaf((float)qop[cb][ks][2 * e], bf16_bits_to_float(kw[e] & 0xffffu), acc);
-                acc = fmaf((float)qop[cb][ks][2 * e + 1], bf16_bits_to_float(kw[e] >> 16), acc);
-              }
-            }
-            dot[jj] = acc + __shfl_xor(acc, 32, 64);
-          }
-        }
-        float m_new = m;
-#pragma unroll
-        for (int jj = 0; jj < UCH; jj++) m_new = fmaxf(m_new, dot[jj]);
-        const float alpha = __builtin_amdgcn_exp2f((m - m_new) * c.c);
-        float pj[UCH], psum = 0.f;
-#pragma unroll
-        for (int jj = 0; jj < UCH; jj++) { pj[jj] = __builtin_amdgcn_exp2f((dot[jj] - m_new) * c.c); psum += pj[jj]; }
-        l = l * alpha + (G == 0 ? psum : 0.f);
-        m = m_new;
-#pragma unroll
-        for (int db = 0; db < D / 32; db++)
-#pragma unroll
-          for (int i = 0; i < 16; i++) o_acc[db][cb][i] *= alpha;
-#pragma unroll
-        for (int jj = 0; jj < UCH; jj++) {
-          if (j0 + jj < c.u) {
-            const uint16_t* vp = c.vu + off0 + jj * jstride + 4 * G;
-            uint2 vv[D / 8];
-#pragma unroll
-            for (int k = 0; k < D / 8; k++) vv[k] = *(const uint2*)(vp + (k / 4) * 32 + 8 * (k % 4));
-#pragma unroll
-            for (int k = 0; k < D / 8; k++) {
-              const int db = k / 4, q4 = k % 4;
-              o_acc[db][cb][4 * q4 + 0] = fmaf(pj[jj], bf16_bits_to_float(vv[k].x & 0xffffu), o_acc[db][cb][4 * q4 + 0]);
-              o_acc[db][cb][4 * q4 + 1] = fmaf(pj[jj], bf16_bits_to_float(vv[k].x >> 16), o_acc[db][cb][4 * q4 + 1]);
-              o_acc[db][cb][4 * q4 + 2] = fmaf(pj[jj], bf16_bits_to_float(vv[k].y & 0xffffu), o_acc[db][cb][4 * q4 + 2]);
-              o_acc[db][cb][4 * q4 + 3] = fmaf(pj[jj], bf16_bits_to_float(vv[k].y >> 16), o_acc[db][cb][4 * q4 + 3]);
-            }
-          }
-        }
-      }
-    }
+    const float m = m_run[cb], l = l_run[cb];
     const float l_tot = l + __shfl_xor(l, 32, 64);
     const size_t orow = ((size_t)b * c.W + w) * c.Hq + hq;
     if (c.nsplit == 1) {
@@ -550,7 +616,9 @@ extern "C" gr_status gr_beam_attn(const gr_attn_params* p, void* workspace, size
   const int64_t groups_padded = ((int64_t)c.n_groups + 7) / 8 * 8;
   const int64_t grid = groups_padded * c.MB;
   if (grid >= ((int64_t)1 << 31)) return GR_ERR_UNSUPPORTED;
-  const size_t lds = (size_t)2 * KT * ((p->d + 8) + (p->d + 16)) * 2;
+  const size_t lds_tiles = (size_t)2 * KT * ((p->d + 8) + (p->d + 16)) * 2;            // K and V tiles, double-buffered, padded rows
+  const size_t lds_own = (size_t)(plan.mwg / 32) * 32 * ((p->d + 8) + (p->d + 16)) * 2;  // one 32-row K and V mini-tile per wave
+  const size_t lds = lds_tiles > lds_own ? lds_tiles : lds_own;
 #define GR_LAUNCH_ATTN(DD, NCB_, NW_)                                                                                        \
   do {                                                                                                                       \
     GR_HIP_TRY(hipFuncSetAttribute((const void*)k_beam_attn<DD, NCB_, NW_>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)); \

@@ -57,6 +57,10 @@ def test_tiny_config_all_steps(gr, oracle_lib):
     (2, 16, 16, 4, 128, 3, (0, 200)),         # an empty prompt: only the beam's own tokens
     (1, 3, 2, 1, 64, 2, (1000,)),             # g=2
     (2, 96, 32, 8, 128, 3, (2048, 1500)),     # the benchmark head geometry; long enough to split L
+    (1, 40, 4, 4, 64, 3, (100,)),             # g=1: 32 beams x 3 own tokens per wave = three unshared mini-tiles
+    (2, 20, 4, 2, 128, 3, (64, 10)),          # g=2: 16 beams x 3 = 48 own-token rows, two mini-tiles
+    (1, 30, 6, 2, 64, 2, (130,)),             # g=3: beams straddle wave boundaries (32 is not a multiple of g)
+    (1, 300, 8, 2, 128, 3, (0,)),             # no prompt at all, several row blocks: own tokens only
 ])
 def test_random_shapes(gr, oracle_lib, B, W, Hq, Hkv, d, u, lens):
     a = rand_attn_case(B * 100 + W, B, W, Hq, Hkv, d, 3, u, lens)
