@@ -26,12 +26,14 @@ constexpr int kRowThreads = 256;
 constexpr int kChunksPerRow = 256;  // chunk keys stored per row (dense rows use all, sparse rows the first 64)
 constexpr int kSelThreads = 1024;
 constexpr int kSparseMax = 256;     // rows with at most this many valid children are gathered, not streamed
+constexpr int kSparseKeys = 64;     // chunk keys of a gathered row (chunk k = children k, k+64, ...)
 constexpr int kListCap = 8192;      // survivors that fit in LDS
 constexpr int kChunkCap = 2048;     // chunks re-read by the fast path
 constexpr int kHistBins = 2048;
 constexpr int kMaxMaskWords = 1024; // V <= 32768
 constexpr int kRegV4 = 8;           // float4 per thread kept in registers (V <= 8192)
-constexpr size_t kSelLdsBytes = (size_t)kListCap * 8 + (size_t)kHistBins * 4 + (size_t)kChunkCap * 4;
+constexpr int kMaxW = 2048;
+constexpr size_t kSelLdsBytes = (size_t)kListCap * 8 + (size_t)kHistBins * 4 + (size_t)kChunkCap * 4 + (size_t)kMaxW * 16;
 
 enum { ROW_DEAD = 0, ROW_DENSE = 1, ROW_SPARSE = 2 };
 
@@ -52,7 +54,7 @@ struct SelCtx {
   int32_t* item_index_out;
   float* row_bias;           // workspace [B*W]
   int32_t* row_mode;         // workspace [B*W]
-  int32_t* row_nvalid;       // workspace [B*W]
+  float* row_top;            // workspace [B*W]: best candidate score of the row (= its largest chunk key)
   float* chunk_key;          // workspace [B*W*kChunksPerRow]
 };
 
@@ -175,18 +177,14 @@ __global__ void __launch_bounds__(kRowThreads) k_row_dense(SelCtx c, int owns_de
   __shared__ uint32_t s_mask[kMaxMaskWords];
   __shared__ float s_redf[kRowThreads / 64];
   __shared__ double s_redd[kRowThreads / 64];
-  __shared__ uint32_t s_redu[kRowThreads / 64];
   __shared__ float s_bias;
   __shared__ double s_tab[64];
   const int row = blockIdx.x;
   const int tid = threadIdx.x;
   const float s_in = c.scores_in[row];
   if (!(s_in > -INFINITY)) {
-    if (owns_dead) {
-      if (tid == 0) { c.row_mode[row] = ROW_DEAD; c.row_bias[row] = -INFINITY; c.row_nvalid[row] = 0; }
-      c.chunk_key[(size_t)row * kChunksPerRow + tid] = -INFINITY;
-    }
-    return;
+    if (owns_dead && tid == 0) { c.row_mode[row] = ROW_DEAD; c.row_bias[row] = -INFINITY; c.row_top[row] = -INFINITY; }
+    return;                                        // the keys of a dead row are never read
   }
   const int V = c.V;
   const int32_t* list = nullptr;
@@ -221,7 +219,6 @@ __global__ void __launch_bounds__(kRowThreads) k_row_dense(SelCtx c, int owns_de
 
   const float* x = c.logits + (size_t)row * V;
   float lmax = -INFINITY;     // this thread's chunk: best valid logit
-  uint32_t nval = 0;
   double S = 0.0;
   float m;
   if (c.vec4 && V <= kRegV4 * 4 * kRowThreads) {
@@ -246,7 +243,6 @@ __global__ void __launch_bounds__(kRowThreads) k_row_dense(SelCtx c, int owns_de
       if (vb[i] & 2u) lmax = fmaxf(lmax, xr[i].y);
       if (vb[i] & 4u) lmax = fmaxf(lmax, xr[i].z);
       if (vb[i] & 8u) lmax = fmaxf(lmax, xr[i].w);
-      nval += __popc(vb[i]);
     }
     m = block_max<kRowThreads / 64>(lmax, s_redf);
     if (m > -INFINITY) {
@@ -264,7 +260,7 @@ __global__ void __launch_bounds__(kRowThreads) k_row_dense(SelCtx c, int owns_de
     const int epc = c.epc;
     for (int e = 0; e < epc; e++) {
       const int v = dense_slot_token(c, tid, e);
-      if (v < V && ((s_mask[v >> 5] >> (v & 31)) & 1u)) { lmax = fmaxf(lmax, x[v]); nval++; }
+      if (v < V && ((s_mask[v >> 5] >> (v & 31)) & 1u)) lmax = fmaxf(lmax, x[v]);
     }
     m = block_max<kRowThreads / 64>(lmax, s_redf);
     if (m > -INFINITY) {
@@ -276,19 +272,17 @@ __global__ void __launch_bounds__(kRowThreads) k_row_dense(SelCtx c, int owns_de
     }
   }
   if (!(m > -INFINITY)) {
-    if (tid == 0) { c.row_mode[row] = ROW_DEAD; c.row_bias[row] = -INFINITY; c.row_nvalid[row] = 0; }
-    c.chunk_key[(size_t)row * kChunksPerRow + tid] = -INFINITY;
+    if (tid == 0) { c.row_mode[row] = ROW_DEAD; c.row_bias[row] = -INFINITY; c.row_top[row] = -INFINITY; }
     return;
   }
   S = block_sum<kRowThreads / 64>(S, s_redd);
-  nval = block_sum_u32<kRowThreads / 64>(nval, s_redu);
   if (tid == 0) {
     const float lse = (float)((double)m + log(S));
     const float bias = __fsub_rn(s_in, lse);
     s_bias = bias;
     c.row_bias[row] = bias;
     c.row_mode[row] = ROW_DENSE;
-    c.row_nvalid[row] = (int32_t)nval;
+    c.row_top[row] = __fadd_rn(bias, m);
   }
   __syncthreads();
   c.chunk_key[(size_t)row * kChunksPerRow + tid] = (lmax > -INFINITY) ? __fadd_rn(s_bias, lmax) : -INFINITY;
@@ -315,12 +309,8 @@ __global__ void __launch_bounds__(kRowThreads) k_row_sparse(SelCtx c) {
     row_children(c, mv, row, &list, &n);
     if (!row_is_sparse(c, n)) return;          // k_row_dense owns this row
   }
-  // every key slot of the row is defined: unused ones hold -inf
-#pragma unroll
-  for (int k = 1; k < kChunksPerRow / 64; k++) keys[lane + 64 * k] = -INFINITY;
   if (!live || n == 0) {
-    if (lane == 0) { c.row_mode[row] = ROW_DEAD; c.row_bias[row] = -INFINITY; c.row_nvalid[row] = 0; }
-    keys[lane] = -INFINITY;
+    if (lane == 0) { c.row_mode[row] = ROW_DEAD; c.row_bias[row] = -INFINITY; c.row_top[row] = -INFINITY; }
     return;
   }
   const float* x = c.logits + (size_t)row * c.V;
@@ -341,8 +331,8 @@ __global__ void __launch_bounds__(kRowThreads) k_row_sparse(SelCtx c) {
   S = gr_wave_sum(S);
   const float lse = (float)((double)m + log(S));
   const float bias = __fsub_rn(s_in, lse);
-  if (lane == 0) { c.row_bias[row] = bias; c.row_mode[row] = ROW_SPARSE; c.row_nvalid[row] = n; }
-  keys[lane] = (lmax > -INFINITY) ? __fadd_rn(bias, lmax) : -INFINITY;
+  if (lane == 0) { c.row_bias[row] = bias; c.row_mode[row] = ROW_SPARSE; c.row_top[row] = __fadd_rn(bias, m); }
+  keys[lane] = (lmax > -INFINITY) ? __fadd_rn(bias, lmax) : -INFINITY;     // a sparse row has kSparseKeys keys
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -393,7 +383,7 @@ __device__ __forceinline__ uint64_t composite(float score, uint32_t flat) {
 
 // Monotone (non-increasing in the score) bin index below the request's best chunk key.
 __device__ __forceinline__ int key_bin(float hi, float score) {
-  return (int)fminf((hi - score) * 64.0f, (float)(kHistBins - 1));
+  return (int)fminf(fmaxf((hi - score) * 64.0f, 0.f), (float)(kHistBins - 1));
 }
 
 // Exact MSB radix select of the W best composite keys over ALL candidates (slow, always correct).
@@ -505,96 +495,174 @@ __global__ void __launch_bounds__(kSelThreads) k_select(SelCtx c) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   uint64_t* s_list = (uint64_t*)smem;
   uint32_t* s_hist = (uint32_t*)(smem + (size_t)kListCap * 8);
-  uint32_t* s_chunks = (uint32_t*)(smem + (size_t)kListCap * 8 + (size_t)kHistBins * 4);
+  uint32_t* s_chunks = s_hist + kHistBins;
+  float* s_rbias = (float*)(s_chunks + kChunkCap);          // per beam row of the request: bias,
+  int32_t* s_rmode = (int32_t*)(s_rbias + kMaxW);            // mode,
+  int32_t* s_ra = s_rmode + kMaxW;                           // first token (step 1) or table range start (step 2),
+  int32_t* s_rb = s_ra + kMaxW;                              // table range end (step 2)
   __shared__ float s_redf[kSelThreads / 64];
-  __shared__ uint32_t s_n, s_nc;
+  __shared__ uint16_t s_live[kMaxW];
+  __shared__ uint32_t s_n, s_nc, s_nlive;
   __shared__ int s_thr;
   const int b = blockIdx.x, tid = threadIdx.x;
   constexpr int NW = kSelThreads / 64;
   MaskView mv;
   if (c.blob) mv = mask_view(c.blob);
 
-  if (tid == 0) { s_n = 0; s_nc = 0; }
-  // ---- threshold from the chunk keys (the best candidate score of every 1/256th of a row)
-  const float4* keys4 = (const float4*)(c.chunk_key + (size_t)b * c.W * kChunksPerRow);
-  const int nk4 = c.W * kChunksPerRow / 4;
-  float hi = -INFINITY;
-  for (int i = tid; i < nk4; i += kSelThreads) {
-    const float4 k = keys4[i];
-    hi = fmaxf(fmaxf(hi, fmaxf(k.x, k.y)), fmaxf(k.z, k.w));
-  }
-  hi = block_max<NW>(hi, s_redf);
+  if (tid == 0) { s_n = 0; s_nc = 0; s_nlive = 0; }
   for (int i = tid; i < kHistBins; i += kSelThreads) s_hist[i] = 0;
   __syncthreads();
+  // ---- the request's rows: what the rows kernels left, the live ones listed, the best candidate overall
+  float hi = -INFINITY;
+  for (int w = tid; w < c.W; w += kSelThreads) {
+    const size_t row = (size_t)b * c.W + w;
+    const int mode = c.row_mode[row];
+    s_rmode[w] = mode;
+    s_rbias[w] = c.row_bias[row];
+    int a = 0, bb = 0;
+    if (mode != ROW_DEAD) {
+      hi = fmaxf(hi, c.row_top[row]);
+      s_live[atomicAdd(&s_nlive, 1u)] = (uint16_t)w;
+      if (c.blob && c.step == 1) {
+        a = c.prefix_in[row * c.depth];
+      } else if (c.blob && c.step == 2) {
+        a = c.range_in[2 * row]; bb = c.range_in[2 * row + 1];
+        if (a < 0 || bb < a || (int64_t)bb > mv.n_items) { a = 0; bb = 0; }
+      }
+    }
+    s_ra[w] = a;
+    s_rb[w] = bb;
+  }
+  hi = block_max<NW>(hi, s_redf);          // (has the barriers that publish the row table)
+  const int nlive = (int)s_nlive;
+
+  // ---- threshold from the chunk keys of the live rows (the best candidate score of every 1/256th of a
+  // streamed row, every 1/64th of a gathered one).  Keys are read once and kept in registers for the
+  // second use when they fit (up to 256 live rows).
+  const float4* keys4 = (const float4*)(c.chunk_key + (size_t)b * c.W * kChunksPerRow);
+  constexpr int KR = 16;                   // float4 of keys per thread held in registers
+  const int ngroups = nlive * (kChunksPerRow / 4);
+  auto group_of = [&](int idx, int* w, int* g) {           // key group idx -> (row, group in row); false if it holds no keys
+    *w = s_live[idx / (kChunksPerRow / 4)];
+    *g = idx % (kChunksPerRow / 4);
+    return s_rmode[*w] == ROW_DENSE || *g < kSparseKeys / 4;
+  };
   int n = 0;
   bool need_fallback = false;
   if (hi > -INFINITY) {
-    for (int i = tid; i < nk4; i += kSelThreads) {
-      const float4 k = keys4[i];
-      if (k.x > -INFINITY) atomicAdd(&s_hist[key_bin(hi, k.x)], 1u);
-      if (k.y > -INFINITY) atomicAdd(&s_hist[key_bin(hi, k.y)], 1u);
-      if (k.z > -INFINITY) atomicAdd(&s_hist[key_bin(hi, k.z)], 1u);
-      if (k.w > -INFINITY) atomicAdd(&s_hist[key_bin(hi, k.w)], 1u);
+    float4 kq[KR];
+#pragma unroll
+    for (int i = 0; i < KR; i++) {
+      const int idx = tid + i * kSelThreads;
+      int w, g;
+      kq[i] = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
+      if (idx < ngroups && group_of(idx, &w, &g)) kq[i] = keys4[(size_t)w * (kChunksPerRow / 4) + g];
+    }
+    auto bin4 = [&](const float4& k, auto&& f) {
+      if (k.x > -INFINITY) f(0, key_bin(hi, k.x));
+      if (k.y > -INFINITY) f(1, key_bin(hi, k.y));
+      if (k.z > -INFINITY) f(2, key_bin(hi, k.z));
+      if (k.w > -INFINITY) f(3, key_bin(hi, k.w));
+    };
+#pragma unroll
+    for (int i = 0; i < KR; i++) bin4(kq[i], [&](int, int bin) { atomicAdd(&s_hist[bin], 1u); });
+    for (int idx = tid + KR * kSelThreads; idx < ngroups; idx += kSelThreads) {
+      int w, g;
+      if (group_of(idx, &w, &g)) bin4(keys4[(size_t)w * (kChunksPerRow / 4) + g], [&](int, int bin) { atomicAdd(&s_hist[bin], 1u); });
     }
     __syncthreads();
     if (tid < 64) hist_threshold(s_hist, (uint32_t)c.W, &s_thr);
     __syncthreads();
     const int thr = s_thr;
     // ---- chunks that reach the threshold
-    for (int i = tid; i < nk4; i += kSelThreads) {
-      const float4 k = keys4[i];
-      const float kk[4] = {k.x, k.y, k.z, k.w};
-#pragma unroll
-      for (int j = 0; j < 4; j++)
-        if (kk[j] > -INFINITY && key_bin(hi, kk[j]) <= thr) {
-          const uint32_t idx = atomicAdd(&s_nc, 1u);
-          if (idx < (uint32_t)kChunkCap) s_chunks[idx] = (uint32_t)(4 * i + j);     // = w * 256 + chunk
+    auto take = [&](int idx, const float4& k) {
+      int w, g;
+      group_of(idx, &w, &g);
+      bin4(k, [&](int j, int bin) {
+        if (bin <= thr) {
+          const uint32_t pos = atomicAdd(&s_nc, 1u);
+          if (pos < (uint32_t)kChunkCap) s_chunks[pos] = ((uint32_t)w << 8) | (uint32_t)(4 * g + j);
         }
+      });
+    };
+#pragma unroll
+    for (int i = 0; i < KR; i++)
+      if (tid + i * kSelThreads < ngroups) take(tid + i * kSelThreads, kq[i]);
+    for (int idx = tid + KR * kSelThreads; idx < ngroups; idx += kSelThreads) {
+      int w, g;
+      if (group_of(idx, &w, &g)) take(idx, keys4[(size_t)w * (kChunksPerRow / 4) + g]);
     }
     __syncthreads();
     const int nc = (int)s_nc;
     if (nc > kChunkCap) {
       need_fallback = true;
     } else {
-      // ---- re-read only those chunks; keep their candidates that reach the threshold
-      const int epc = max(c.epc, kSparseMax / 64);
-      for (int idx = tid; idx < nc * epc; idx += kSelThreads) {
-        const uint32_t ent = s_chunks[idx / epc];
-        const int e = idx % epc;
-        const int w = (int)(ent >> 8), k = (int)(ent & 255u);
-        const int row = b * c.W + w;
-        int v = -1;
-        if (c.row_mode[row] == ROW_DENSE) {
-          if (e < c.epc) {
-            const int t = dense_slot_token(c, k, e);
-            if (t < c.V) {
-              bool ok = true;
-              if (c.blob) {
-                if (c.step == 0) ok = (mv.l0[t >> 5] >> (t & 31)) & 1u;
+      // ---- re-read only those chunks; keep their candidates that reach the threshold.  Four
+      // (chunk, element) slots per thread and round, all of their loads issued before any is used.
+      const int epc = max(c.epc, kSparseMax / kSparseKeys);
+      const int total = nc * epc;
+      constexpr int U = 4;
+      for (int base = 0; base < total; base += U * kSelThreads) {
+        int wv[U], tok[U];
+        float x[U];
+        uint32_t bits[U];
+        const int32_t* lst[U];
+        int nl[U];
+#pragma unroll
+        for (int q = 0; q < U; q++) {
+          const int idx = base + q * kSelThreads + tid;
+          tok[q] = -1; x[q] = 0.f; bits[q] = 0; lst[q] = nullptr; nl[q] = 0; wv[q] = 0;
+          if (idx < total) {
+            const uint32_t ent = s_chunks[idx / epc];
+            const int e = idx % epc;
+            const int w = (int)(ent >> 8), k = (int)(ent & 255u);
+            wv[q] = w;
+            const float* xrow = c.logits + ((size_t)b * c.W + w) * c.V;
+            if (s_rmode[w] == ROW_DENSE) {
+              const int t = (e < c.epc) ? dense_slot_token(c, k, e) : c.V;
+              if (t < c.V) {
+                tok[q] = t;
+                x[q] = xrow[t];
+                if (!c.blob) bits[q] = 1u;
+                else if (c.step == 0) bits[q] = (mv.l0[t >> 5] >> (t & 31)) & 1u;
                 else if (c.step == 1) {
-                  const int t1 = c.prefix_in[(size_t)row * c.depth];
-                  ok = (mv.l1[(size_t)t1 * mv.words + (t >> 5)] >> (t & 31)) & 1u;
-                } else {
-                  const int32_t* list; int nl;
-                  row_children(c, mv, row, &list, &nl);
-                  const int pos = lower_bound_i32(list, nl, t);
-                  ok = pos < nl && list[pos] == t;
-                }
+                  const int t1 = s_ra[w];
+                  bits[q] = (t1 >= 0 && t1 < c.V) ? ((mv.l1[(size_t)t1 * mv.words + (t >> 5)] >> (t & 31)) & 1u) : 0u;
+                } else { lst[q] = mv.t3 + s_ra[w]; nl[q] = s_rb[w] - s_ra[w]; }
               }
-              if (ok) v = t;
+            } else {
+              // gathered row: chunk k = children k, k + 64, ...
+              const int32_t* list;
+              int nlist;
+              if (c.step == 1) {
+                const int t1 = s_ra[w];
+                const bool ok = t1 >= 0 && t1 < c.V;
+                const int p0 = ok ? mv.pair_off[t1] : 0, p1 = ok ? mv.pair_off[t1 + 1] : 0;
+                list = mv.pair_t2 + p0; nlist = p1 - p0;
+              } else { list = mv.t3 + s_ra[w]; nlist = s_rb[w] - s_ra[w]; }
+              const int i = k + kSparseKeys * e;
+              if (k < kSparseKeys && e < kSparseMax / kSparseKeys && i < nlist) {
+                const int t = list[i];
+                tok[q] = t;
+                x[q] = xrow[t];
+                bits[q] = 1u;
+              }
             }
           }
-        } else {
-          const int32_t* list; int nl;
-          row_children(c, mv, row, &list, &nl);
-          const int i = k + 64 * e;
-          if (e < kSparseMax / 64 && i < nl) v = list[i];
         }
-        if (v >= 0) {
-          const float score = __fadd_rn(c.row_bias[row], c.logits[(size_t)row * c.V + v]);
+#pragma unroll
+        for (int q = 0; q < U; q++) {
+          if (tok[q] < 0) continue;
+          bool ok = bits[q] != 0;
+          if (lst[q]) {                     // last level, streamed row: membership in the row's short child list
+            const int pos = lower_bound_i32(lst[q], nl[q], tok[q]);
+            ok = pos < nl[q] && lst[q][pos] == tok[q];
+          }
+          if (!ok) continue;
+          const float score = __fadd_rn(s_rbias[wv[q]], x[q]);
           if (key_bin(hi, score) <= thr) {
             const uint32_t pos = atomicAdd(&s_n, 1u);
-            if (pos < (uint32_t)kListCap) s_list[pos] = composite(score, (uint32_t)w * (uint32_t)c.V + (uint32_t)v);
+            if (pos < (uint32_t)kListCap) s_list[pos] = composite(score, (uint32_t)wv[q] * (uint32_t)c.V + (uint32_t)tok[q]);
           }
         }
       }
@@ -730,7 +798,7 @@ extern "C" gr_status gr_beam_select(const gr_select_params* p, void* workspace, 
   char* ws = (char*)workspace;
   c.row_bias = (float*)ws;                 ws += gr_align256(rows * 4);
   c.row_mode = (int32_t*)ws;               ws += gr_align256(rows * 4);
-  c.row_nvalid = (int32_t*)ws;             ws += gr_align256(rows * 4);
+  c.row_top = (float*)ws;                  ws += gr_align256(rows * 4);
   c.chunk_key = (float*)ws;
 
   const bool has_sparse = p->mask && p->step >= 1 && !(p->flags & GR_SELECT_FORCE_DENSE);
