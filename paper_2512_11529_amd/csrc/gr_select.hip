@@ -703,21 +703,42 @@ __global__ void __launch_bounds__(kSelThreads) k_select(SelCtx c) {
   }
 
   // ---- order the survivors (descending composite key = score descending, flat index ascending)
+  const uint64_t* s_sorted = s_list;
   int n2 = 1;
   while (n2 < n) n2 <<= 1;
-  for (int i = n + tid; i < n2; i += kSelThreads) s_list[i] = 0;   // 0 sorts after every real key
-  __syncthreads();
-  for (int k = 2; k <= n2; k <<= 1) {
-    for (int j = k >> 1; j > 0; j >>= 1) {
-      for (int i = tid; i < n2; i += kSelThreads) {
-        const int ixj = i ^ j;
-        if (ixj > i) {
-          const uint64_t a = s_list[i], bb = s_list[ixj];
-          const bool desc = (i & k) == 0;
-          if (desc ? (a < bb) : (a > bb)) { s_list[i] = bb; s_list[ixj] = a; }
+  if (n2 < kSelThreads / 64) n2 = kSelThreads / 64;      // at most one wavefront per key below
+  if (n2 <= kSelThreads / 2) {
+    // few survivors (the usual case, about W of them): rank every key by counting the larger ones,
+    // kSelThreads / n2 threads per key, each scanning its share of the list.  Keys are distinct.
+    const int parts = kSelThreads / n2;                  // a power of two >= 2
+    const int i = tid / parts, part = tid % parts;
+    const int len = (n + parts - 1) / parts;
+    uint32_t cnt = 0;
+    if (i < n) {
+      const uint64_t mine = s_list[i];
+      const int j1 = min(n, (part + 1) * len);
+      for (int j = part * len; j < j1; j++) cnt += s_list[j] > mine;
+    }
+    for (int o = 1; o < parts; o <<= 1) cnt += __shfl_xor(cnt, o, 64);   // parts <= 64 consecutive lanes hold one key
+    uint64_t* s_out = s_list + kListCap / 2;             // n <= kSelThreads / 2 <= kListCap / 2: no overlap
+    if (i < n && part == 0) s_out[cnt] = s_list[i];
+    s_sorted = s_out;
+    __syncthreads();
+  } else {
+    for (int i = n + tid; i < n2; i += kSelThreads) s_list[i] = 0;   // 0 sorts after every real key
+    __syncthreads();
+    for (int k = 2; k <= n2; k <<= 1) {
+      for (int j = k >> 1; j > 0; j >>= 1) {
+        for (int i = tid; i < n2; i += kSelThreads) {
+          const int ixj = i ^ j;
+          if (ixj > i) {
+            const uint64_t a = s_list[i], bb = s_list[ixj];
+            const bool desc = (i & k) == 0;
+            if (desc ? (a < bb) : (a > bb)) { s_list[i] = bb; s_list[ixj] = a; }
+          }
         }
+        __syncthreads();
       }
-      __syncthreads();
     }
   }
 
@@ -728,7 +749,7 @@ __global__ void __launch_bounds__(kSelThreads) k_select(SelCtx c) {
     for (int k = 0; k < c.depth; k++) po[k] = -1;
     int r_lo = 0, r_hi = 0, item = -1;
     if (j < n) {
-      const uint64_t key = s_list[j];
+      const uint64_t key = s_sorted[j];
       const uint32_t flat = 0xffffffffu - (uint32_t)key;
       const int parent = (int)(flat / (uint32_t)c.V), token = (int)(flat % (uint32_t)c.V);
       c.parent_out[o] = parent;
