@@ -545,23 +545,24 @@ __global__ void __launch_bounds__(256) k_attn_merge(AttnCtx c) {
   if (c.lse && lane == 0) c.lse[row] = (L > 0.f) ? (M2 + __builtin_amdgcn_logf(L)) * kLn2 : -INFINITY;
 }
 
-// Host-side launch plan.  Big problems use 8-wave workgroups of 256 query rows (each K/V tile staged
-// once per 256 rows); small ones use 4-wave workgroups of 128 rows, two per CU, so that more units
-// exist and one workgroup's prologue overlaps the other's main loop.  When there are still too few
-// units to fill 256 CUs a few times over, the prompt is split into L segments (merged by k_attn_merge).
+// Host-side launch plan, fitted to a measured sweep over (B, L, W) on the MI355X.  8-wave workgroups
+// of 256 query rows stage each K/V tile once per 256 rows and win whenever a (request, KV head) has
+// more than 128 rows.  Splitting the prompt into L segments costs fp32 partials through HBM plus the
+// merge kernel, so it only pays while it fills idle CUs: segments are added until about one
+// workgroup per CU exists (never fewer than four tiles per segment), and not at all once 256 units
+// exist without it.
 struct AttnPlan { int mwg, nsplit; };
 AttnPlan plan_attn(const gr_attn_params* p) {
   const int g = p->Hq / p->Hkv;
   const int64_t M = (int64_t)p->W * g;
-  const int64_t units256 = (int64_t)p->B * p->Hkv * ((M + 255) / 256);
   AttnPlan plan;
-  plan.mwg = units256 >= 256 ? 256 : 128;
+  plan.mwg = M <= 128 ? 128 : 256;
   const int64_t units = (int64_t)p->B * p->Hkv * ((M + plan.mwg - 1) / plan.mwg);
   plan.nsplit = 1;
-  if (units < 512 && p->max_L > 4 * KT) {
-    int64_t want = (1024 + units - 1) / units;
-    int64_t cap = p->max_L / (4 * KT);     // at least four tiles per segment
-    int64_t n = want < cap ? want : cap;
+  if (units < 256 && p->max_L > 4 * KT) {
+    const int64_t want = (256 + units / 2) / units;       // nearest to one workgroup per CU
+    const int64_t cap = p->max_L / (4 * KT);              // at least four tiles per segment
+    const int64_t n = want < cap ? want : cap;
     plan.nsplit = (int)(n > 16 ? 16 : (n < 1 ? 1 : n));
   }
   return plan;

@@ -61,6 +61,8 @@ def test_tiny_config_all_steps(gr, oracle_lib):
     (2, 20, 4, 2, 128, 3, (64, 10)),          # g=2: 16 beams x 3 = 48 own-token rows, two mini-tiles
     (1, 30, 6, 2, 64, 2, (130,)),             # g=3: beams straddle wave boundaries (32 is not a multiple of g)
     (1, 300, 8, 2, 128, 3, (0,)),             # no prompt at all, several row blocks: own tokens only
+    (1, 200, 4, 2, 64, 2, (300,)),            # d=64 with more than 128 rows per KV head: the 8-wave d=64 kernel
+    (1, 8, 8, 2, 128, 1, (1500,)),            # 32 rows per KV head, long prompt: 4-wave kernel with L split in five
 ])
 def test_random_shapes(gr, oracle_lib, B, W, Hq, Hkv, d, u, lens):
     a = rand_attn_case(B * 100 + W, B, W, Hq, Hkv, d, 3, u, lens)
