@@ -56,7 +56,7 @@ def main():
                          "readings of the same run can be scaled")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU; requests shard across GPUs with no exchange (see DESIGN.md), "
+        print("bench.py: this build runs on ONE GPU; requests are independent and would shard across GPUs with no exchange, "
               "so --gpus must be 1", file=sys.stderr)
         sys.exit(2)
 
