@@ -87,6 +87,16 @@ def test_structured_inputs_give_order_one_outputs(gr, oracle_lib):
     _check(gr, oracle_lib, a, 1.0)
 
 
+def test_wide_beam_sampled_rows(gr, oracle_lib):
+    # W = 2048 beams (8192 query rows per KV head, 32 row blocks): sampled outputs against the oracle
+    B, W, Hq, Hkv, d = 1, 2048, 8, 2, 64
+    a = rand_attn_case(31, B, W, Hq, Hkv, d, 3, 3, (200,))
+    rng = np.random.default_rng(3)
+    tri = np.stack([np.zeros(300, np.int64), rng.integers(0, W, 300), rng.integers(0, Hq, 300)], axis=1).astype(np.int32)
+    tri[:4] = [[0, 0, 0], [0, W - 1, Hq - 1], [0, 255, 3], [0, 256, 4]]
+    _check(gr, oracle_lib, a, float(np.float32(1 / np.sqrt(d))), tri)
+
+
 def test_separated_cache_is_w_independent_of_other_beams(gr, oracle_lib):
     # changing one beam's own tokens must not change any other beam's output
     a = rand_attn_case(9, 1, 6, 4, 2, 64, 3, 2, (90,))

@@ -122,6 +122,23 @@ def test_unconstrained_all_beams_live(gr, oracle_lib, B, W, V):
     assert_select_equal(got, want)
 
 
+def test_maximum_sizes(gr, oracle_lib):
+    """The documented limits: W = 2048 beams (more live rows than the selection kernel keeps keys for in
+    registers, more survivors than the counting sort takes) and V = 32768 (the widest mask row)."""
+    rng = np.random.default_rng(77)
+    B, W, V = 1, 2048, 1024
+    logits = (2.0 * rng.standard_normal((B, W, V))).astype(np.float32)
+    sc = (-3.0 * rng.random((B, W))).astype(np.float32)
+    pf = np.full((B, W, 3), -1, np.int32)
+    rg = np.zeros((B, W, 2), np.int32)
+    assert_select_equal(run_select(gr, None, logits, sc, pf, rg, 0), oracle_lib.beam_select(None, logits, sc, pf, 0))
+    items = _random_table(rng, 4096, 400000)
+    _three_steps(gr, oracle_lib, items, lambda s: (2.5 * rng.standard_normal((1, 600, 4096))).astype(np.float32), 1, 600, 4096)
+    items = _random_table(rng, 32768, 100000)
+    _three_steps(gr, oracle_lib, items, lambda s: (2.5 * rng.standard_normal((2, 8, 32768))).astype(np.float32), 2, 8, 32768)
+    _three_steps(gr, oracle_lib, items, lambda s: (2.5 * rng.standard_normal((2, 8, 32768))).astype(np.float32), 2, 8, 32768, flags=1)
+
+
 def test_ties_resolved_by_lowest_flat_index(gr, oracle_lib):
     rng = np.random.default_rng(11)
     B, W, V = 2, 12, 300
