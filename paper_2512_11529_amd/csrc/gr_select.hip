@@ -1,11 +1,12 @@
 // gr_beam_select: beam item step (paper Sections 6.1-6.3) on gfx950.
 //
-// Kernels per call (no host synchronisation, no allocation; everything lives in caller buffers):
-//   k_row_dense    one workgroup per beam row that is streamed in full: validity bits staged in LDS
-//                  (dense level-0 / level-1 mask rows, or the row's sparse last-level positions set
-//                  in an empty mask), logits read ONCE with 16-byte loads and kept in registers for
-//                  the max, the fp64 sum-exp and the per-chunk maxima.
-//   k_row_sparse   one wavefront per beam row with few valid children: gathers only those logits.
+// Two kernels per call (no host synchronisation, no allocation; everything lives in caller buffers):
+//   k_rows         both kinds of beam row in one launch:
+//                  streamed rows, one workgroup each: validity bits staged in LDS (dense level-0 /
+//                  level-1 mask rows, or the row's sparse last-level positions set in an empty mask),
+//                  logits read ONCE with 16-byte loads and kept in registers for the max, the fp64
+//                  sum-exp and the per-chunk maxima;
+//                  gathered rows (few valid children), one wavefront each: only those logits are read.
 //   k_select       one workgroup per request: top-W of the request's candidates by (score descending,
 //                  flat index ascending).  It never sorts the W*V candidates: the rows kernels leave
 //                  one "chunk key" (best candidate score) per 1/256th of a row; a histogram of those
@@ -173,13 +174,12 @@ __device__ __forceinline__ uint32_t block_sum_u32(uint32_t v, uint32_t* s_red) {
 // ------------------------------------------------------------------------------------------------
 // Rows that are streamed in full.
 // ------------------------------------------------------------------------------------------------
-__global__ void __launch_bounds__(kRowThreads) k_row_dense(SelCtx c, int owns_dead) {
+__device__ __forceinline__ void row_dense(const SelCtx& c, int owns_dead, int row) {
   __shared__ uint32_t s_mask[kMaxMaskWords];
   __shared__ float s_redf[kRowThreads / 64];
   __shared__ double s_redd[kRowThreads / 64];
   __shared__ float s_bias;
   __shared__ double s_tab[64];
-  const int row = blockIdx.x;
   const int tid = threadIdx.x;
   const float s_in = c.scores_in[row];
   if (!(s_in > -INFINITY)) {
@@ -194,7 +194,7 @@ __global__ void __launch_bounds__(kRowThreads) k_row_dense(SelCtx c, int owns_de
     mv = mask_view(c.blob);
     if (c.step >= 1) {
       row_children(c, mv, row, &list, &n_list);
-      if (row_is_sparse(c, n_list)) return;      // k_row_sparse owns this row
+      if (row_is_sparse(c, n_list)) return;      // a gathered row: rows_sparse owns it
     }
   }
   if (tid < 64) s_tab[tid] = exp2((double)tid * (1.0 / 64.0));
@@ -292,11 +292,11 @@ __global__ void __launch_bounds__(kRowThreads) k_row_dense(SelCtx c, int owns_de
 // Rows with few valid children: one wavefront each, gather only the valid logits (Section 6.1's
 // sparse form).  Chunk k of such a row = children k, k+64, k+128, ...
 // ------------------------------------------------------------------------------------------------
-__global__ void __launch_bounds__(kRowThreads) k_row_sparse(SelCtx c) {
+__device__ __forceinline__ void rows_sparse(const SelCtx& c, int group) {
   __shared__ double s_tab[64];
   if (threadIdx.x < 64) s_tab[threadIdx.x] = exp2((double)threadIdx.x * (1.0 / 64.0));
   __syncthreads();
-  const int row = blockIdx.x * (kRowThreads / 64) + (threadIdx.x >> 6);
+  const int row = group * (kRowThreads / 64) + (threadIdx.x >> 6);
   const int lane = threadIdx.x & 63;
   if (row >= c.B * c.W) return;
   float* keys = c.chunk_key + (size_t)row * kChunksPerRow;
@@ -307,7 +307,7 @@ __global__ void __launch_bounds__(kRowThreads) k_row_sparse(SelCtx c) {
   const bool live = s_in > -INFINITY;
   if (live) {
     row_children(c, mv, row, &list, &n);
-    if (!row_is_sparse(c, n)) return;          // k_row_dense owns this row
+    if (!row_is_sparse(c, n)) return;          // a streamed row: row_dense owns it
   }
   if (!live || n == 0) {
     if (lane == 0) { c.row_mode[row] = ROW_DEAD; c.row_bias[row] = -INFINITY; c.row_top[row] = -INFINITY; }
@@ -333,6 +333,14 @@ __global__ void __launch_bounds__(kRowThreads) k_row_sparse(SelCtx c) {
   const float bias = __fsub_rn(s_in, lse);
   if (lane == 0) { c.row_bias[row] = bias; c.row_mode[row] = ROW_SPARSE; c.row_top[row] = __fadd_rn(bias, m); }
   keys[lane] = (lmax > -INFINITY) ? __fadd_rn(bias, lmax) : -INFINITY;     // a sparse row has kSparseKeys keys
+}
+
+// One launch for both kinds of row: the first n_dense_blocks workgroups stream one row each (those come
+// first because they run longest), the rest gather four sparse rows each.  Every row is looked at by
+// both kinds; the shared test row_is_sparse decides which of them owns it.
+__global__ void __launch_bounds__(kRowThreads) k_rows(SelCtx c, int owns_dead, int n_dense_blocks) {
+  if ((int)blockIdx.x < n_dense_blocks) row_dense(c, owns_dead, (int)blockIdx.x);
+  else rows_sparse(c, (int)blockIdx.x - n_dense_blocks);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -823,9 +831,8 @@ extern "C" gr_status gr_beam_select(const gr_select_params* p, void* workspace, 
   c.chunk_key = (float*)ws;
 
   const bool has_sparse = p->mask && p->step >= 1 && !(p->flags & GR_SELECT_FORCE_DENSE);
-  if (has_sparse)
-    hipLaunchKernelGGL(k_row_sparse, dim3((unsigned)((rows + 3) / 4)), dim3(kRowThreads), 0, stream, c);
-  hipLaunchKernelGGL(k_row_dense, dim3((unsigned)rows), dim3(kRowThreads), 0, stream, c, has_sparse ? 0 : 1);
+  const size_t sparse_blocks = has_sparse ? (rows + kRowThreads / 64 - 1) / (kRowThreads / 64) : 0;
+  hipLaunchKernelGGL(k_rows, dim3((unsigned)(rows + sparse_blocks)), dim3(kRowThreads), 0, stream, c, has_sparse ? 0 : 1, (int)rows);
   // more than 64 KB of LDS must be opted into (per device; cheap, so done on every call)
   GR_HIP_TRY(hipFuncSetAttribute((const void*)k_select, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kSelLdsBytes));
   hipLaunchKernelGGL(k_select, dim3(p->B), dim3(kSelThreads), kSelLdsBytes, stream, c);
