@@ -572,8 +572,15 @@ __global__ void __launch_bounds__(kSelThreads) k_select(SelCtx c) {
       if (k.z > -INFINITY) f(2, key_bin(hi, k.z));
       if (k.w > -INFINITY) f(3, key_bin(hi, k.w));
     };
+    uint32_t kb[KR][2];                    // bins of the register-resident keys, 16 bits each (0xffff: no key)
 #pragma unroll
-    for (int i = 0; i < KR; i++) bin4(kq[i], [&](int, int bin) { atomicAdd(&s_hist[bin], 1u); });
+    for (int i = 0; i < KR; i++) {
+      kb[i][0] = 0xffffffffu; kb[i][1] = 0xffffffffu;
+      bin4(kq[i], [&](int j, int bin) {
+        atomicAdd(&s_hist[bin], 1u);
+        kb[i][j >> 1] = (j & 1) ? ((kb[i][j >> 1] & 0x0000ffffu) | ((uint32_t)bin << 16)) : ((kb[i][j >> 1] & 0xffff0000u) | (uint32_t)bin);
+      });
+    }
     for (int idx = tid + KR * kSelThreads; idx < ngroups; idx += kSelThreads) {
       int w, g;
       if (group_of(idx, &w, &g)) bin4(keys4[(size_t)w * (kChunksPerRow / 4) + g], [&](int, int bin) { atomicAdd(&s_hist[bin], 1u); });
@@ -594,8 +601,20 @@ __global__ void __launch_bounds__(kSelThreads) k_select(SelCtx c) {
       });
     };
 #pragma unroll
-    for (int i = 0; i < KR; i++)
-      if (tid + i * kSelThreads < ngroups) take(tid + i * kSelThreads, kq[i]);
+    for (int i = 0; i < KR; i++) {
+      const uint32_t b4[4] = {kb[i][0] & 0xffffu, kb[i][0] >> 16, kb[i][1] & 0xffffu, kb[i][1] >> 16};
+      const uint32_t thr_u = (uint32_t)thr;
+      if (b4[0] <= thr_u || b4[1] <= thr_u || b4[2] <= thr_u || b4[3] <= thr_u) {      // (0xffff never passes)
+        int w, g;
+        group_of(tid + i * kSelThreads, &w, &g);
+#pragma unroll
+        for (int j = 0; j < 4; j++)
+          if (b4[j] <= thr_u) {
+            const uint32_t pos = atomicAdd(&s_nc, 1u);
+            if (pos < (uint32_t)kChunkCap) s_chunks[pos] = ((uint32_t)w << 8) | (uint32_t)(4 * g + j);
+          }
+      }
+    }
     for (int idx = tid + KR * kSelThreads; idx < ngroups; idx += kSelThreads) {
       int w, g;
       if (group_of(idx, &w, &g)) take(idx, keys4[(size_t)w * (kChunksPerRow / 4) + g]);
@@ -609,7 +628,7 @@ __global__ void __launch_bounds__(kSelThreads) k_select(SelCtx c) {
       // (chunk, element) slots per thread and round, all of their loads issued before any is used.
       const int epc = max(c.epc, kSparseMax / kSparseKeys);
       const int total = nc * epc;
-      constexpr int U = 4;
+      constexpr int U = 8;
       for (int base = 0; base < total; base += U * kSelThreads) {
         int wv[U], tok[U];
         float x[U];
@@ -714,22 +733,25 @@ __global__ void __launch_bounds__(kSelThreads) k_select(SelCtx c) {
   const uint64_t* s_sorted = s_list;
   int n2 = 1;
   while (n2 < n) n2 <<= 1;
-  if (n2 < kSelThreads / 64) n2 = kSelThreads / 64;      // at most one wavefront per key below
-  if (n2 <= kSelThreads / 2) {
+  if (n > 0 && n <= kSelThreads / 2) {
     // few survivors (the usual case, about W of them): rank every key by counting the larger ones,
-    // kSelThreads / n2 threads per key, each scanning its share of the list.  Keys are distinct.
-    const int parts = kSelThreads / n2;                  // a power of two >= 2
+    // kSelThreads / n threads per key, each scanning its share of the list.  Keys are distinct.
+    const int parts = kSelThreads / n;
     const int i = tid / parts, part = tid % parts;
     const int len = (n + parts - 1) / parts;
-    uint32_t cnt = 0;
+    uint32_t* s_rank = s_hist;                            // (the histogram is no longer needed)
+    for (int k = tid; k < n; k += kSelThreads) s_rank[k] = 0;
+    __syncthreads();
     if (i < n) {
       const uint64_t mine = s_list[i];
       const int j1 = min(n, (part + 1) * len);
+      uint32_t cnt = 0;
       for (int j = part * len; j < j1; j++) cnt += s_list[j] > mine;
+      if (cnt) atomicAdd(&s_rank[i], cnt);
     }
-    for (int o = 1; o < parts; o <<= 1) cnt += __shfl_xor(cnt, o, 64);   // parts <= 64 consecutive lanes hold one key
+    __syncthreads();
     uint64_t* s_out = s_list + kListCap / 2;             // n <= kSelThreads / 2 <= kListCap / 2: no overlap
-    if (i < n && part == 0) s_out[cnt] = s_list[i];
+    if (tid < n) s_out[s_rank[tid]] = s_list[tid];
     s_sorted = s_out;
     __syncthreads();
   } else {
