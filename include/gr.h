@@ -78,7 +78,8 @@ typedef struct {
 /* Bytes of workspace gr_beam_attn needs for these shapes (0 is possible).  Host only. */
 size_t gr_beam_attn_workspace_bytes(const gr_attn_params* p);
 
-/* Enqueue the attention.  `workspace` (device, 256-byte aligned) holds split-L partials; contents
+/* Enqueue the attention.  `workspace` (device, 256-byte aligned) holds split-L partials and, for a
+ * ragged batch, the order in which requests are dispatched (longest prompt first); contents
  * before and after the call are unspecified.  Errors: INVALID_ARG, UNSUPPORTED,
  * WORKSPACE_TOO_SMALL, HIP. */
 gr_status gr_beam_attn(const gr_attn_params* p, void* workspace, size_t workspace_bytes, void* stream);

@@ -118,9 +118,11 @@ def _attn_params(q, k_shared, v_shared, cu_seqlens, k_unshared, v_unshared, u, s
     return p
 
 
-def attn_workspace_bytes(B, W, Hq, Hkv, d, max_L) -> int:
+def attn_workspace_bytes(B, W, Hq, Hkv, d, max_L, total_L=None) -> int:
+    """Workspace bytes of gr_beam_attn.  Without total_L the batch is taken as ragged (the larger answer)."""
     p = _AttnParams()
     p.B, p.W, p.Hq, p.Hkv, p.d, p.max_L = B, W, Hq, Hkv, d, int(max_L)
+    p.total_L = int(total_L) if total_L is not None else max(0, B * int(max_L) - 1)
     return int(load_library().gr_beam_attn_workspace_bytes(ctypes.byref(p)))
 
 

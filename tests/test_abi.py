@@ -45,7 +45,8 @@ def test_size_queries(gr):
     assert lib.gr_item_mask_bytes(10, 2, 8) == 0 and lib.gr_item_mask_bytes(0, 3, 8) == 0
     assert lib.gr_item_mask_bytes(10, 3, 40000) == 0
     assert lib.gr_beam_select_workspace_bytes(32, 256, 8192, 3) >= 2 * 32 * 256 * 4
-    assert gr.attn_workspace_bytes(32, 256, 32, 8, 128, 4096) == 0            # enough work units without splitting L
+    assert gr.attn_workspace_bytes(32, 256, 32, 8, 128, 4096, total_L=32 * 4096) == 0   # uniform batch, enough units: nothing
+    assert gr.attn_workspace_bytes(32, 256, 32, 8, 128, 4096, total_L=32 * 4096 - 5) == 256  # ragged: the dispatch order of 32 requests
     assert gr.attn_workspace_bytes(1, 256, 32, 8, 128, 4096) > 0              # one request cannot fill the chip: split L
 
 
