@@ -51,6 +51,16 @@ __device__ __forceinline__ float bf16_bits_to_float(uint32_t h) { return __uint_
 
 __device__ __forceinline__ bf16x8 as_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8, v); }
 
+// n / d and n % d for 0 <= n < 2^22 and a small runtime divisor, through a float reciprocal and one
+// correction step (a handful of instructions where the generic 32-bit division takes dozens).
+__device__ __forceinline__ void divmod_small(int n, int d, float rcp_d, int* q, int* r) {
+  int qq = (int)((float)n * rcp_d);
+  int rr = n - qq * d;
+  if (rr >= d) { qq++; rr -= d; }
+  if (rr < 0) { qq--; rr += d; }
+  *q = qq; *r = rr;
+}
+
 // Per-tile building blocks.  A tile is KT = 64 prompt tokens; S^T of a tile is [64 kv x 32*NCB q]
 // = 2 sub-tiles x NCB column blocks of 32x32 fp32 accumulators.
 template <int D, int NCB>
@@ -204,21 +214,27 @@ k_beam_attn(AttnCtx c) {
   const int seg0 = min(Lb, sp * chunk), seg1 = min(Lb, seg0 + chunk);
   const int ntiles = (seg1 - seg0 + KT - 1) / KT;
 
-  // ---- Q as B operands: lane holds query column n32 of block cb, d = 16*ks + 8*G + (0..7)
-  bf16x8 qop[NCB][D / 16];
+  // ---- Q: the workgroup's MWG query rows are fetched with coalesced 16-byte pieces (a row = PPR
+  // consecutive lanes) and handed to the lanes that own them through LDS.  A lane reading its own
+  // row straight from global memory touches 32 different rows per load instruction, which keeps the
+  // address unit busy for microseconds while the CU has nothing else to do.
+  static_assert(NCB == 1, "one column block per wave");
+  constexpr int QP = MWG * PPR / NT;             // 16-byte pieces of Q per thread
+  const float rcp_g = 1.0f / (float)c.g;
+  uint4 qpiece[QP];
+#pragma unroll
+  for (int i = 0; i < QP; i++) {
+    const int p = tid + i * NT, rl = p / PPR, col = (p % PPR) * 8;
+    const int r = mbi * MWG + rl;
+    int w, j;
+    divmod_small(r, c.g, rcp_g, &w, &j);
+    qpiece[i] = make_uint4(0, 0, 0, 0);
+    if (r < c.M) qpiece[i] = *(const uint4*)(c.q + (((size_t)b * c.W + w) * c.Hq + kvh * c.g + j) * D + col);
+  }
   int qrow[NCB];       // local query row or -1
-#pragma unroll
-  for (int cb = 0; cb < NCB; cb++) {
-    const int r = mbi * MWG + wave * 32 * NCB + cb * 32 + n32;
-    qrow[cb] = (r < c.M) ? r : -1;
-    const int w = r / c.g, j = r % c.g;
-    const uint16_t* qp = c.q + (((size_t)b * c.W + w) * c.Hq + kvh * c.g + j) * D + G * 8;
-#pragma unroll
-    for (int ks = 0; ks < D / 16; ks++) {
-      uint4 v = make_uint4(0, 0, 0, 0);
-      if (r < c.M) v = *(const uint4*)(qp + ks * 16);
-      qop[cb][ks] = as_bf16x8(v);
-    }
+  {
+    const int r = mbi * MWG + wave * 32 + n32;
+    qrow[0] = (r < c.M) ? r : -1;
   }
 
   f32x16 o_acc[D / 32][NCB];
@@ -307,14 +323,32 @@ k_beam_attn(AttnCtx c) {
     }
   };
 
+  // first prompt tiles: requested before anything waits on memory
+  Stage k1;
+  if (ntiles > 0) {
+    kreg = gload(kbase, 0); vreg = gload(vbase, 0);
+    k1 = gload(kbase, min(1, ntiles - 1));
+  }
+  // Q as B operands: lane holds query column n32 of the wave's block, d = 16*ks + 8*G + (0..7)
+  bf16x8 qop[NCB][D / 16];
+  {
+#pragma unroll
+    for (int i = 0; i < QP; i++) {
+      const int p = tid + i * NT, rl = p / PPR, col = (p % PPR) * 8;
+      *(uint4*)(&smem[rl * KSTR + col]) = qpiece[i];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int ks = 0; ks < D / 16; ks++) qop[0][ks] = as_bf16x8(*(const uint4*)(&smem[(wave * 32 + n32) * KSTR + ks * 16 + G * 8]));
+    __syncthreads();                                 // the tile slots may now be overwritten
+  }
+
   if (ntiles > 0) {
     // Pipeline: iteration t issues S(t+1) = K(t+1).Q^T together with the softmax of S(t), then O += V(t).P(t).
     // K(t+2) and V(t+1) are written to LDS right after the barrier that opens iteration t, so one
     // barrier per tile orders every buffer reuse.  Loads for tiles past the end are clamped to the
     // last tile (harmless re-reads; a duplicate K tile lands in a buffer nobody reads any more).
     const int tl = ntiles - 1;
-    kreg = gload(kbase, 0); vreg = gload(vbase, 0);
-    Stage k1 = gload(kbase, min(1, tl));
     lstore(s_k, KSTR, kreg); lstore(s_v, VSTR, vreg);
     lstore(s_k + KT * KSTR, KSTR, k1);
     kreg = gload(kbase, min(2, tl));
@@ -620,7 +654,7 @@ extern "C" gr_status gr_beam_attn(const gr_attn_params* p, void* workspace, size
   if (p->total_L >= ((int64_t)1 << 31)) return GR_ERR_UNSUPPORTED;
   if ((int64_t)p->max_L * p->Hkv * p->d * 2 >= ((int64_t)1 << 32)) return GR_ERR_UNSUPPORTED;   // one request's K (or V) must fit a buffer descriptor
   const int g = p->Hq / p->Hkv;
-  if ((int64_t)p->W * g >= ((int64_t)1 << 30)) return GR_ERR_UNSUPPORTED;
+  if ((int64_t)p->W * g >= ((int64_t)1 << 22)) return GR_ERR_UNSUPPORTED;      // row indices go through divmod_small
 
   AttnCtx c;
   c.B = p->B; c.W = p->W; c.Hq = p->Hq; c.Hkv = p->Hkv; c.g = g; c.ND = p->ND; c.u = p->u;
