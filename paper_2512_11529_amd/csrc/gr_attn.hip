@@ -506,39 +506,53 @@ k_beam_attn(AttnCtx c) {
   }
 
   // ---- epilogue: merge is already done in registers; normalise or write this segment's partials
-#pragma unroll
-  for (int cb = 0; cb < NCB; cb++) {
-    const int r = qrow[cb];
-    if (r < 0) continue;
-    const int w = r / c.g, j = r % c.g;
-    const int hq = kvh * c.g + j;
-    const float m = m_run[cb], l = l_run[cb];
+  {
+    const int r = qrow[0];
+    const float m = m_run[0], l = l_run[0];
     const float l_tot = l + __shfl_xor(l, 32, 64);
-    const size_t orow = ((size_t)b * c.W + w) * c.Hq + hq;
     if (c.nsplit == 1) {
+      // The wave's 32 rows x D outputs go through its own slice of LDS so that global memory sees whole
+      // 256-byte rows (16 lanes x 16 bytes) instead of 8-byte pieces of 32 different rows per store.
+      if (!own_stage && ntiles > 0) __syncthreads();       // nobody reads the tile slots any more
+      uint16_t* s_o = smem + wave * 32 * KSTR;
       const float inv = (l_tot > 0.f) ? 1.0f / l_tot : 0.f;
-      uint16_t* op = c.out + orow * D + 4 * G;
 #pragma unroll
       for (int db = 0; db < D / 32; db++)
 #pragma unroll
         for (int q4 = 0; q4 < 4; q4++) {
-          f32x2 a = {o_acc[db][cb][4 * q4] * inv, o_acc[db][cb][4 * q4 + 1] * inv};
-          f32x2 bb = {o_acc[db][cb][4 * q4 + 2] * inv, o_acc[db][cb][4 * q4 + 3] * inv};
+          f32x2 a = {o_acc[db][0][4 * q4] * inv, o_acc[db][0][4 * q4 + 1] * inv};
+          f32x2 bb = {o_acc[db][0][4 * q4 + 2] * inv, o_acc[db][0][4 * q4 + 3] * inv};
           bf16x2 ha = __builtin_convertvector(a, bf16x2), hb = __builtin_convertvector(bb, bf16x2);
           uint2 st;
           st.x = __builtin_bit_cast(uint32_t, ha);
           st.y = __builtin_bit_cast(uint32_t, hb);
-          *(uint2*)(op + db * 32 + 8 * q4) = st;
+          *(uint2*)(&s_o[n32 * KSTR + db * 32 + 8 * q4 + 4 * G]) = st;
         }
-      if (c.lse && G == 0) c.lse[orow] = (l_tot > 0.f) ? (m * c.c + __builtin_amdgcn_logf(l_tot)) * kLn2 : -INFINITY;
-    } else {
+      const float rcp_g2 = 1.0f / (float)c.g;
+#pragma unroll
+      for (int i = 0; i < 32 * PPR / 64; i++) {
+        const int p = lane + 64 * i, rl = p / PPR, col = (p % PPR) * 8;
+        const int rr = mbi * MWG + wave * 32 + rl;
+        int w, j;
+        divmod_small(rr, c.g, rcp_g2, &w, &j);
+        const uint4 v = *(const uint4*)(&s_o[rl * KSTR + col]);
+        if (rr < c.M) *(uint4*)(c.out + (((size_t)b * c.W + w) * c.Hq + kvh * c.g + j) * D + col) = v;
+      }
+      if (c.lse && G == 0 && r >= 0) {
+        int w, j;
+        divmod_small(r, c.g, rcp_g2, &w, &j);
+        c.lse[((size_t)b * c.W + w) * c.Hq + kvh * c.g + j] = (l_tot > 0.f) ? (m * c.c + __builtin_amdgcn_logf(l_tot)) * kLn2 : -INFINITY;
+      }
+    } else if (r >= 0) {
+      const int w = r / c.g, j = r % c.g;
+      const int hq = kvh * c.g + j;
       const size_t prow = ((size_t)b * c.nsplit + sp) * ((size_t)c.W * c.Hq) + (size_t)w * c.Hq + hq;
       float* pp = c.part_o + prow * D + 4 * G;
 #pragma unroll
       for (int db = 0; db < D / 32; db++)
 #pragma unroll
         for (int q4 = 0; q4 < 4; q4++) {
-          f32x4 st = {o_acc[db][cb][4 * q4], o_acc[db][cb][4 * q4 + 1], o_acc[db][cb][4 * q4 + 2], o_acc[db][cb][4 * q4 + 3]};
+          f32x4 st = {o_acc[db][0][4 * q4], o_acc[db][0][4 * q4 + 1], o_acc[db][0][4 * q4 + 2], o_acc[db][0][4 * q4 + 3]};
           *(f32x4*)(pp + db * 32 + 8 * q4) = st;
         }
       if (G == 0) {
