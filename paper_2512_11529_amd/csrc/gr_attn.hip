@@ -221,6 +221,7 @@ k_beam_attn(AttnCtx c) {
   static_assert(NCB == 1, "one column block per wave");
   constexpr int QP = MWG * PPR / NT;             // 16-byte pieces of Q per thread
   const float rcp_g = 1.0f / (float)c.g;
+  const uint16_t* q_b = c.q + (size_t)b * c.W * c.Hq * D;      // this request's queries; offsets inside it fit 32 bits
   uint4 qpiece[QP];
 #pragma unroll
   for (int i = 0; i < QP; i++) {
@@ -229,7 +230,7 @@ k_beam_attn(AttnCtx c) {
     int w, j;
     divmod_small(r, c.g, rcp_g, &w, &j);
     qpiece[i] = make_uint4(0, 0, 0, 0);
-    if (r < c.M) qpiece[i] = *(const uint4*)(c.q + (((size_t)b * c.W + w) * c.Hq + kvh * c.g + j) * D + col);
+    if (r < c.M) qpiece[i] = *(const uint4*)(q_b + (uint32_t)((w * c.Hq + kvh * c.g + j) * D + col));
   }
   int qrow[NCB];       // local query row or -1
   {
@@ -301,13 +302,18 @@ k_beam_attn(AttnCtx c) {
   };
   int beam0 = 0, npass = 0, R = 0;
   if (own_stage) {
-    for (int wv = 0; wv < NWAVES; wv++) { int fb; npass = max(npass, (wave_rows(wv, &fb) + UR - 1) / UR); }
+    // the most beams any wave's 32 rows can span (exact when g divides 32, else an upper bound: a surplus
+    // pass only sees masked rows)
+    const int nb_max = (32 % c.g == 0) ? 32 / c.g : (32 + c.g - 2) / c.g + 1;
+    npass = (nb_max * c.u + UR - 1) / UR;
     R = wave_rows(wave, &beam0);
   }
   const int my_lo = (qrow[0] >= 0) ? (qrow[0] / c.g - beam0) * c.u : -1;         // this column's rows [my_lo, my_lo + u)
   uint4 ukp[UP], uvp[UP];
+  const float rcp_u = 1.0f / (float)max(c.u, 1);
   auto uload = [&](int pass) {                           // 32 rows x D/8 pieces per tensor; a row = PPR consecutive lanes
-    const size_t tok_elems = (size_t)c.Hkv * D;
+    const uint16_t* ku_b = c.ku + (size_t)b * c.W * c.ND * c.Hkv * D;      // this request's own-token caches
+    const uint16_t* vu_b = c.vu + (size_t)b * c.W * c.ND * c.Hkv * D;
 #pragma unroll
     for (int i = 0; i < UP; i++) {
       const int pi = lane + 64 * i, row = pi / PPR, col = (pi % PPR) * 8;
@@ -315,10 +321,11 @@ k_beam_attn(AttnCtx c) {
       ukp[i] = make_uint4(0, 0, 0, 0);
       uvp[i] = make_uint4(0, 0, 0, 0);
       if (rho < R) {
-        const int bl = rho / c.u, tok = rho - bl * c.u;
-        const size_t off = (((size_t)b * c.W + beam0 + bl) * c.ND + tok) * tok_elems + (size_t)kvh * D + col;
-        ukp[i] = *(const uint4*)(c.ku + off);
-        uvp[i] = *(const uint4*)(c.vu + off);
+        int bl, tok;
+        divmod_small(rho, c.u, rcp_u, &bl, &tok);
+        const uint32_t off = (uint32_t)(((beam0 + bl) * c.ND + tok) * (c.Hkv * D) + kvh * D + col);
+        ukp[i] = *(const uint4*)(ku_b + off);
+        uvp[i] = *(const uint4*)(vu_b + off);
       }
     }
   };
@@ -529,6 +536,7 @@ k_beam_attn(AttnCtx c) {
           *(uint2*)(&s_o[n32 * KSTR + db * 32 + 8 * q4 + 4 * G]) = st;
         }
       const float rcp_g2 = 1.0f / (float)c.g;
+      uint16_t* out_b = c.out + (size_t)b * c.W * c.Hq * D;
 #pragma unroll
       for (int i = 0; i < 32 * PPR / 64; i++) {
         const int p = lane + 64 * i, rl = p / PPR, col = (p % PPR) * 8;
@@ -536,7 +544,7 @@ k_beam_attn(AttnCtx c) {
         int w, j;
         divmod_small(rr, c.g, rcp_g2, &w, &j);
         const uint4 v = *(const uint4*)(&s_o[rl * KSTR + col]);
-        if (rr < c.M) *(uint4*)(c.out + (((size_t)b * c.W + w) * c.Hq + kvh * c.g + j) * D + col) = v;
+        if (rr < c.M) *(uint4*)(out_b + (uint32_t)((w * c.Hq + kvh * c.g + j) * D + col)) = v;
       }
       if (c.lse && G == 0 && r >= 0) {
         int w, j;
@@ -669,6 +677,8 @@ extern "C" gr_status gr_beam_attn(const gr_attn_params* p, void* workspace, size
   if ((int64_t)p->max_L * p->Hkv * p->d * 2 >= ((int64_t)1 << 32)) return GR_ERR_UNSUPPORTED;   // one request's K (or V) must fit a buffer descriptor
   const int g = p->Hq / p->Hkv;
   if ((int64_t)p->W * g >= ((int64_t)1 << 22)) return GR_ERR_UNSUPPORTED;      // row indices go through divmod_small
+  if ((int64_t)p->W * p->Hq * p->d >= ((int64_t)1 << 31) || (int64_t)p->W * p->ND * p->Hkv * p->d >= ((int64_t)1 << 31))
+    return GR_ERR_UNSUPPORTED;                                                   // offsets inside one request fit 32 bits
 
   AttnCtx c;
   c.B = p->B; c.W = p->W; c.Hq = p->Hq; c.Hkv = p->Hkv; c.g = g; c.ND = p->ND; c.u = p->u;
