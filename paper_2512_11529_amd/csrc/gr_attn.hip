@@ -551,19 +551,39 @@ k_beam_attn(AttnCtx c) {
         divmod_small(r, c.g, rcp_g2, &w, &j);
         c.lse[((size_t)b * c.W + w) * c.Hq + kvh * c.g + j] = (l_tot > 0.f) ? (m * c.c + __builtin_amdgcn_logf(l_tot)) * kLn2 : -INFINITY;
       }
-    } else if (r >= 0) {
-      const int w = r / c.g, j = r % c.g;
-      const int hq = kvh * c.g + j;
-      const size_t prow = ((size_t)b * c.nsplit + sp) * ((size_t)c.W * c.Hq) + (size_t)w * c.Hq + hq;
-      float* pp = c.part_o + prow * D + 4 * G;
+    } else {
+      // this segment's unnormalised fp32 partial O and (max, sum): staged through LDS like the final
+      // output, half of the columns at a time
+      if (!own_stage && ntiles > 0) __syncthreads();       // nobody reads the tile slots any more
+      float* s_p = (float*)(smem + wave * 32 * KSTR);
+      constexpr int CW = D / 2;                            // columns per round: a wave's slice holds 32 rows x CW floats
+      constexpr int PSTR = KSTR / 2;                       // floats per staged row (CW + padding)
+      const float rcp_g2 = 1.0f / (float)c.g;
+      float* part_b = c.part_o + ((size_t)b * c.nsplit + sp) * ((size_t)c.W * c.Hq) * D;
 #pragma unroll
-      for (int db = 0; db < D / 32; db++)
+      for (int h = 0; h < 2; h++) {
 #pragma unroll
-        for (int q4 = 0; q4 < 4; q4++) {
-          f32x4 st = {o_acc[db][0][4 * q4], o_acc[db][0][4 * q4 + 1], o_acc[db][0][4 * q4 + 2], o_acc[db][0][4 * q4 + 3]};
-          *(f32x4*)(pp + db * 32 + 8 * q4) = st;
+        for (int dd = 0; dd < CW / 32; dd++)
+#pragma unroll
+          for (int q4 = 0; q4 < 4; q4++) {
+            const int db = h * (CW / 32) + dd;
+            const f32x4 st = {o_acc[db][0][4 * q4], o_acc[db][0][4 * q4 + 1], o_acc[db][0][4 * q4 + 2], o_acc[db][0][4 * q4 + 3]};
+            *(f32x4*)(&s_p[n32 * PSTR + dd * 32 + 8 * q4 + 4 * G]) = st;
+          }
+#pragma unroll
+        for (int i = 0; i < CW / 8; i++) {
+          const int p = lane + 64 * i, rl = p / (CW / 4), col = (p % (CW / 4)) * 4;
+          const int rr = mbi * MWG + wave * 32 + rl;
+          int w, j;
+          divmod_small(rr, c.g, rcp_g2, &w, &j);
+          const f32x4 v = *(const f32x4*)(&s_p[rl * PSTR + col]);
+          if (rr < c.M) *(f32x4*)(part_b + (size_t)(w * c.Hq + kvh * c.g + j) * D + h * CW + col) = v;
         }
-      if (G == 0) {
+      }
+      if (G == 0 && r >= 0) {
+        int w, j;
+        divmod_small(r, c.g, rcp_g2, &w, &j);
+        const size_t prow = ((size_t)b * c.nsplit + sp) * ((size_t)c.W * c.Hq) + (size_t)w * c.Hq + kvh * c.g + j;
         f32x2 ml = {(l_tot > 0.f) ? m * c.c : -INFINITY, l_tot};
         *(f32x2*)(c.part_ml + prow * 2) = ml;
       }
