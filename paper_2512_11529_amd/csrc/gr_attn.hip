@@ -197,19 +197,22 @@ k_beam_attn(AttnCtx c) {
 
   // XCD-aware unit order: workgroups are dealt round-robin to the 8 XCDs, so ids congruent mod 8
   // share an L2.  The MB row blocks that read the same K/V stream get consecutive slots of one XCD.
-  const int id = blockIdx.x;
-  const int xcd = id & 7, slot = id >> 3;
-  const int group = (slot / c.MB) * 8 + xcd;
-  const int mbi = slot % c.MB;
+  // (unsigned arithmetic: these scalar divisions run once per workgroup, but every wave runs them)
+  const unsigned id = blockIdx.x;
+  const int xcd = (int)(id & 7u);
+  const unsigned slot = id >> 3;
+  const int group = (int)(slot / (unsigned)c.MB) * 8 + xcd;
+  const int mbi = (int)(slot % (unsigned)c.MB);
   if (group >= c.n_groups) return;
-  const int sp = group % c.nsplit;
-  const int kvh = (group / c.nsplit) % c.Hkv;
-  const int bi = group / (c.nsplit * c.Hkv);
+  const unsigned gq = (unsigned)group / (unsigned)c.nsplit;
+  const int sp = (int)((unsigned)group - gq * (unsigned)c.nsplit);
+  const int bi = (int)(gq / (unsigned)c.Hkv);
+  const int kvh = (int)(gq - (unsigned)bi * (unsigned)c.Hkv);
   const int b = c.order ? c.order[bi] : bi;
 
   const int row0 = c.cu[b];
   const int Lb = c.cu[b + 1] - row0;
-  int chunk = (Lb + c.nsplit - 1) / c.nsplit;
+  int chunk = (int)(((unsigned)Lb + (unsigned)c.nsplit - 1u) / (unsigned)c.nsplit);
   chunk = ((chunk + KT - 1) / KT) * KT;
   const int seg0 = min(Lb, sp * chunk), seg1 = min(Lb, seg0 + chunk);
   const int ntiles = (seg1 - seg0 + KT - 1) / KT;
