@@ -123,13 +123,22 @@ __device__ __forceinline__ int lower_bound_i32(const int32_t* a, int n, int key)
 // exp(y) = 2^n' * 2^(j/64) * (1 + r + r^2/2 + ... + r^5/120).  `tab` holds 2^(j/64), j = 0..63.
 // Far cheaper than a general-purpose exp; its error is ~1e-16 relative, which the fp64 sum of a
 // row carries unchanged into the single fp32 rounding of lse.
-__device__ __forceinline__ double exp_nonpos(double y, const double* tab) {
-  const double nf = rint(y * 92.33248261689366);              // 64 / ln 2
-  double r = fma(nf, -0x1.62e42fee00000p-7, y);                // ln2/64, high 32 bits (exact product)
-  r = fma(nf, -0x1.a39ef35793c76p-39, r);                      // ln2/64, low part
-  double p = fma(r, 1.0 / 120.0, 1.0 / 24.0);
-  p = fma(p, r, 1.0 / 6.0);
-  p = fma(p, r, 0.5);
+// The polynomial and range-reduction constants live in scalar registers (set up once per kernel):
+// left to itself the compiler re-materialises each 64-bit constant with vector moves inside every
+// conditional block that evaluates an exponential.
+struct ExpConsts { double inv_step, step_hi, step_lo, c5, c4, c3, c2; };
+__device__ __forceinline__ ExpConsts exp_consts() {
+  ExpConsts k = {92.33248261689366, -0x1.62e42fee00000p-7, -0x1.a39ef35793c76p-39, 1.0 / 120.0, 1.0 / 24.0, 1.0 / 6.0, 0.5};
+  asm volatile("" : "+s"(k.inv_step), "+s"(k.step_hi), "+s"(k.step_lo), "+s"(k.c5), "+s"(k.c4), "+s"(k.c3), "+s"(k.c2));
+  return k;
+}
+__device__ __forceinline__ double exp_nonpos(double y, const double* tab, const ExpConsts& k) {
+  const double nf = rint(y * k.inv_step);                      // 64 / ln 2
+  double r = fma(nf, k.step_hi, y);                            // ln2/64, high 32 bits (exact product)
+  r = fma(nf, k.step_lo, r);                                   // ln2/64, low part
+  double p = fma(r, k.c5, k.c4);
+  p = fma(p, r, k.c3);
+  p = fma(p, r, k.c2);
   p = fma(p, r, 1.0);
   p = p * r;
   const int n = (int)nf;
@@ -198,6 +207,7 @@ __device__ __forceinline__ void row_dense(const SelCtx& c, int owns_dead, int ro
     }
   }
   if (tid < 64) s_tab[tid] = exp2((double)tid * (1.0 / 64.0));
+  const ExpConsts ek = exp_consts();
   // ---- validity bits of the row in LDS
   const int words = (V + 31) >> 5;
   if (!c.blob) {
@@ -249,10 +259,10 @@ __device__ __forceinline__ void row_dense(const SelCtx& c, int owns_dead, int ro
       const double md = (double)m;
 #pragma unroll
       for (int i = 0; i < kRegV4; i++) {
-        if (vb[i] & 1u) S += exp_nonpos((double)xr[i].x - md, s_tab);
-        if (vb[i] & 2u) S += exp_nonpos((double)xr[i].y - md, s_tab);
-        if (vb[i] & 4u) S += exp_nonpos((double)xr[i].z - md, s_tab);
-        if (vb[i] & 8u) S += exp_nonpos((double)xr[i].w - md, s_tab);
+        if (vb[i] & 1u) S += exp_nonpos((double)xr[i].x - md, s_tab, ek);
+        if (vb[i] & 2u) S += exp_nonpos((double)xr[i].y - md, s_tab, ek);
+        if (vb[i] & 4u) S += exp_nonpos((double)xr[i].z - md, s_tab, ek);
+        if (vb[i] & 8u) S += exp_nonpos((double)xr[i].w - md, s_tab, ek);
       }
     }
   } else {
@@ -267,7 +277,7 @@ __device__ __forceinline__ void row_dense(const SelCtx& c, int owns_dead, int ro
       const double md = (double)m;
       for (int e = 0; e < epc; e++) {
         const int v = dense_slot_token(c, tid, e);
-        if (v < V && ((s_mask[v >> 5] >> (v & 31)) & 1u)) S += exp_nonpos((double)x[v] - md, s_tab);
+        if (v < V && ((s_mask[v >> 5] >> (v & 31)) & 1u)) S += exp_nonpos((double)x[v] - md, s_tab, ek);
       }
     }
   }
@@ -295,6 +305,7 @@ __device__ __forceinline__ void row_dense(const SelCtx& c, int owns_dead, int ro
 __device__ __forceinline__ void rows_sparse(const SelCtx& c, int group) {
   __shared__ double s_tab[64];
   if (threadIdx.x < 64) s_tab[threadIdx.x] = exp2((double)threadIdx.x * (1.0 / 64.0));
+  const ExpConsts ek = exp_consts();
   __syncthreads();
   const int row = group * (kRowThreads / 64) + (threadIdx.x >> 6);
   const int lane = threadIdx.x & 63;
@@ -327,7 +338,7 @@ __device__ __forceinline__ void rows_sparse(const SelCtx& c, int group) {
   const double md = (double)m;
 #pragma unroll
   for (int k = 0; k < kSparseMax / 64; k++)
-    if (lane + 64 * k < n) S += exp_nonpos((double)xv[k] - md, s_tab);
+    if (lane + 64 * k < n) S += exp_nonpos((double)xv[k] - md, s_tab, ek);
   S = gr_wave_sum(S);
   const float lse = (float)((double)m + log(S));
   const float bias = __fsub_rn(s_in, lse);
