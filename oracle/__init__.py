@@ -144,3 +144,20 @@ def unshared_reorder(kv, parent):
     if rc != 0:
         raise RuntimeError(f"oracle_unshared_reorder failed: {rc}")
     return kv
+
+
+def unshared_reorder_two_sweeps(kv, parent):
+    """The paper's own in-place procedure (direction index per row, upward writes walking down, then the rest
+    walking up).  Needs live rows first with non-decreasing parents; raises ValueError otherwise.
+    Returns (kv, direction int32 [B,W])."""
+    B, W = parent.shape
+    row = int(np.prod(kv.shape[2:]))
+    parent = np.ascontiguousarray(parent, dtype=np.int32)
+    direction = np.zeros((B, W), dtype=np.int32)
+    rc = _load().oracle_unshared_reorder_two_sweeps(ctypes.c_int(B), ctypes.c_int(W), ctypes.c_int64(row),
+                                                    _p(parent, np.int32), _p(kv, np.uint16), _p(direction, np.int32))
+    if rc == -1:
+        raise ValueError("two-sweep reorder needs live rows first and non-decreasing parents")
+    if rc != 0:
+        raise RuntimeError(f"oracle_unshared_reorder_two_sweeps failed: {rc}")
+    return kv, direction

@@ -354,6 +354,54 @@ int oracle_unshared_reorder(int B, int W, int64_t row_elems, const int32_t *pare
     return ORACLE_OK;
 }
 
+/* ------------------------------------------------------------------------------------------------
+ * Second, independent reorder: the in-place procedure Section 5.1 itself describes.  One buffer, no
+ * temporary copy of the cache.  Every row j gets a direction index: +1 when its write moves a block
+ * upward (the source row parent[j] lies below the target, parent[j] > j), -1 when it moves a block
+ * downward (parent[j] < j), 0 when the block stays.  First all upward writes are performed walking
+ * down the rows (j increasing), then the remaining writes walking up (j decreasing).
+ *
+ * The procedure presumes what beam order gives the paper: the live rows come first and their parents
+ * are non-decreasing; then no block is overwritten before its last reader has copied it.  Anything
+ * else is rejected with ORACLE_ERR_ARG (the buffer is then untouched).  Dead rows (parent < 0), which
+ * must follow the live ones, are zero-filled after both sweeps (reading taken here: the paper does
+ * not say what a dead slot holds).
+ * direction_out: int32 [B, W], may be NULL.
+ * ------------------------------------------------------------------------------------------------ */
+int oracle_unshared_reorder_two_sweeps(int B, int W, int64_t row_elems, const int32_t *parent, uint16_t *kv,
+                                       int32_t *direction_out) {
+    if (B <= 0 || W <= 0 || row_elems <= 0) return ORACLE_ERR_ARG;
+    for (int b = 0; b < B; b++) {
+        const int32_t *p = parent + (int64_t)b * W;
+        int n_live = 0;
+        while (n_live < W && p[n_live] >= 0) n_live++;
+        for (int j = 0; j < W; j++) {
+            if (j >= n_live && p[j] >= 0) return ORACLE_ERR_ARG;           /* a live row after a dead one */
+            if (j < n_live && p[j] >= W) return ORACLE_ERR_ARG;
+            if (j > 0 && j < n_live && p[j] < p[j - 1]) return ORACLE_ERR_ARG; /* parents must not decrease */
+        }
+    }
+    const size_t row_bytes = sizeof(uint16_t) * (size_t)row_elems;
+    for (int b = 0; b < B; b++) {
+        const int32_t *p = parent + (int64_t)b * W;
+        uint16_t *base = kv + (int64_t)b * W * row_elems;
+        int n_live = 0;
+        while (n_live < W && p[n_live] >= 0) n_live++;
+        for (int j = 0; j < W; j++) {
+            const int dir = (j >= n_live || p[j] == j) ? 0 : (p[j] > j ? 1 : -1);
+            if (direction_out) direction_out[(int64_t)b * W + j] = dir;
+        }
+        /* upward writes, in downward order */
+        for (int j = 0; j < n_live; j++)
+            if (p[j] > j) memcpy(base + (int64_t)j * row_elems, base + (int64_t)p[j] * row_elems, row_bytes);
+        /* the remaining writes, in upward order */
+        for (int j = n_live - 1; j >= 0; j--)
+            if (p[j] < j) memcpy(base + (int64_t)j * row_elems, base + (int64_t)p[j] * row_elems, row_bytes);
+        for (int j = n_live; j < W; j++) memset(base + (int64_t)j * row_elems, 0, row_bytes);
+    }
+    return ORACLE_OK;
+}
+
 int oracle_num_threads(void) {
 #ifdef _OPENMP
     extern int omp_get_max_threads(void);

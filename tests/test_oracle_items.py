@@ -286,16 +286,3 @@ def test_invariants_on_tiny_config(oracle_lib):
             assert (hi == len(items) or tuple(items[hi, :step + 1]) != tuple(r["prefix"][0, j, :step + 1]))
         sc, pf = r["scores"], r["prefix"]
     np.testing.assert_array_equal(items[r["item_index"][0]], r["prefix"][0])
-
-
-def test_unshared_reorder_is_a_gather(oracle_lib):
-    rng = np.random.default_rng(0)
-    B, W, ND, Hkv, d = 2, 6, 3, 2, 4
-    kv = rng.integers(0, 60000, size=(B, W, ND, Hkv, d)).astype(np.uint16)
-    parent = np.array([[3, 3, 0, 5, 1, 1], [0, 1, 2, 3, 4, -1]], dtype=np.int32)
-    want = kv.copy()
-    for b in range(B):
-        for j in range(W):
-            want[b, j] = kv[b, parent[b, j]] if parent[b, j] >= 0 else 0
-    got = oracle_lib.unshared_reorder(kv.copy(), parent)
-    np.testing.assert_array_equal(got, want)
