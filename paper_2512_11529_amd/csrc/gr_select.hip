@@ -1,20 +1,27 @@
-// gr_beam_select: beam item step (paper Sections 6.1-6.3) on gfx950.
+// gr_beam_select: beam item step (paper Sections 6.1-6.3) on gfx950, one fused kernel.
 //
-// Two kernels per call (no host synchronisation, no allocation; everything lives in caller buffers):
-//   k_rows         both kinds of beam row in one launch:
-//                  streamed rows, one workgroup each: validity bits staged in LDS (dense level-0 /
+// k_item       grid = B requests x G workgroups; a workgroup owns kRowsPerWG consecutive beam rows of one
+//              request and walks them one after the other:
+//                streamed rows (all four wavefronts): validity bits staged in LDS (dense level-0 /
 //                  level-1 mask rows, or the row's sparse last-level positions set in an empty mask),
 //                  logits read ONCE with 16-byte loads and kept in registers for the max, the fp64
-//                  sum-exp and the per-chunk maxima;
-//                  gathered rows (few valid children), one wavefront each: only those logits are read.
-//   k_select       one workgroup per request: top-W of the request's candidates by (score descending,
-//                  flat index ascending).  It never sorts the W*V candidates: the rows kernels leave
-//                  one "chunk key" (best candidate score) per 1/256th of a row; a histogram of those
-//                  keys yields a threshold that at least W candidates reach, only the chunks that
-//                  reach it are re-read, and only their candidates above the threshold are sorted
-//                  (the early-termination idea of Section 6.2: stop as soon as the survivors are
-//                  fixed).  If the survivors do not fit in LDS (massive ties) an exact MSB radix
-//                  select over all candidates takes over.
+//                  sum-exp and the candidate scan;
+//                gathered rows (few valid children), one wavefront each: only those logits are read.
+//              Selection never sorts the W*V candidates and never re-reads a logit.  Every workgroup
+//              keeps a small pool of candidates in LDS together with a threshold tau that at least W
+//              known candidates reach; a row appends only its candidates >= tau (a handful per row once
+//              tau has settled), the pool is thinned with a histogram whenever it fills, and tau only
+//              rises - the early-termination idea of Section 6.2 (stop looking at anything that can no
+//              longer enter the top W) in data-parallel form.  tau is shared between the workgroups of
+//              a request through one atomic word.  A finished workgroup publishes its <= W + slack
+//              survivors and takes a ticket; the LAST workgroup of a request to arrive merges the
+//              published lists, orders the final W exactly (score descending, flat index ascending)
+//              and writes the new beam state.  No workgroup ever waits for another.
+//              If a pool overflows (tens of thousands of exact ties) the last workgroup falls back to an
+//              exact MSB radix select over all candidates of the request.
+// k_item_init  clears the per-request control words (ticket, list length, shared tau, overflow flag).
+//              k_item leaves them cleared again, so a caller that reuses a workspace may skip it
+//              (GR_SELECT_WORKSPACE_CLEAN).
 //
 // Arithmetic that decides beam order is fixed: m = fp32 max over valid logits, S = fp64 sum of
 // exp(x - m), lse = fp32(m + log S), bias = score_in - lse (fp32), cand = bias + x (fp32), with no
@@ -23,25 +30,38 @@
 
 namespace {
 
-constexpr int kRowThreads = 256;
-constexpr int kChunksPerRow = 256;  // chunk keys stored per row (dense rows use all, sparse rows the first 64)
-constexpr int kSelThreads = 1024;
-constexpr int kSparseMax = 256;     // rows with at most this many valid children are gathered, not streamed
-constexpr int kSparseKeys = 64;     // chunk keys of a gathered row (chunk k = children k, k+64, ...)
-constexpr int kListCap = 8192;      // survivors that fit in LDS
-constexpr int kChunkCap = 2048;     // chunks re-read by the fast path
+constexpr int kT = 256;              // threads per workgroup
+constexpr int kNW = kT / 64;
+constexpr int kRowsPerWG = 8;        // beam rows a workgroup walks
+constexpr int kSparseMax = 256;      // rows with at most this many valid children are gathered, not streamed
 constexpr int kHistBins = 2048;
-constexpr int kMaxMaskWords = 1024; // V <= 32768
-constexpr int kRegV4 = 8;           // float4 per thread kept in registers (V <= 8192)
+constexpr int kMaxMaskWords = 1024;  // V <= 32768
+constexpr int kRegV4 = 8;            // float4 per thread kept in registers (V <= 8192)
+constexpr int kQueueMax = kHistBins; // valid logits of a streamed row compacted before exponentiation (shares the histogram's LDS)
 constexpr int kMaxW = 2048;
-constexpr size_t kSelLdsBytes = (size_t)kListCap * 8 + (size_t)kHistBins * 4 + (size_t)kChunkCap * 4 + (size_t)kMaxW * 16;
+constexpr int kFlushSlack = 256;     // a workgroup publishes at most W + kFlushSlack survivors
+constexpr int kCtlWords = 8;         // control words per request
+enum { CTL_TICKET = 0, CTL_COUNT = 1, CTL_TAU = 2, CTL_OVERFLOW = 3 };
 
 enum { ROW_DEAD = 0, ROW_DENSE = 1, ROW_SPARSE = 2 };
 
+// Phase timestamps of every workgroup (100 MHz wall clock), debug builds only.
+#ifdef GR_TIMELINE
+#define GR_TL(c, k) do { if ((c).dbg && threadIdx.x == 0) (c).dbg[(size_t)blockIdx.x * 32 + (k)] = wall_clock64(); } while (0)
+#else
+#define GR_TL(c, k) do { } while (0)
+#endif
+
 struct SelCtx {
+#ifdef GR_TIMELINE
+  unsigned long long* dbg;
+#endif
   int B, W, V, depth, step, flags;
-  int vec4;                  // V % 4 == 0: rows are 16-byte aligned, chunks interleave float4 groups
-  int epc;                   // element slots per chunk of a dense row
+  int vec4;                  // V % 4 == 0 and rows 16-byte aligned
+  int G;                     // workgroups per request
+  int cap;                   // candidates a workgroup's LDS pool holds
+  int flush_cap;             // candidates a workgroup may publish
+  int words;                 // ceil(V / 32)
   const char* blob;          // mask blob or nullptr
   const float* logits;
   const float* scores_in;
@@ -55,8 +75,8 @@ struct SelCtx {
   int32_t* item_index_out;
   float* row_bias;           // workspace [B*W]
   int32_t* row_mode;         // workspace [B*W]
-  float* row_top;            // workspace [B*W]: best candidate score of the row (= its largest chunk key)
-  float* chunk_key;          // workspace [B*W*kChunksPerRow]
+  uint32_t* ctl;             // workspace [B*kCtlWords]
+  uint64_t* list;            // workspace [B][G*flush_cap] published survivors
 };
 
 struct MaskView {
@@ -69,20 +89,22 @@ struct MaskView {
   const int32_t* t3;
   int words;
   int64_t n_items;
+  bool ok;                   // header matches the call (magic, V, depth)
 };
 
-__device__ __forceinline__ MaskView mask_view(const char* blob) {
-  const gr_mask_header* h = (const gr_mask_header*)blob;
+__device__ __forceinline__ MaskView mask_view(const SelCtx& c) {
+  const gr_mask_header* h = (const gr_mask_header*)c.blob;
   MaskView m;
-  m.l0 = (const uint32_t*)(blob + h->off_l0);
-  m.l1 = (const uint32_t*)(blob + h->off_l1);
-  m.off1 = (const int32_t*)(blob + h->off_off1);
-  m.pair_off = (const int32_t*)(blob + h->off_pair_off);
-  m.pair_t2 = (const int32_t*)(blob + h->off_pair_t2);
-  m.pair_row = (const int32_t*)(blob + h->off_pair_row);
-  m.t3 = (const int32_t*)(blob + h->off_t3);
+  m.l0 = (const uint32_t*)(c.blob + h->off_l0);
+  m.l1 = (const uint32_t*)(c.blob + h->off_l1);
+  m.off1 = (const int32_t*)(c.blob + h->off_off1);
+  m.pair_off = (const int32_t*)(c.blob + h->off_pair_off);
+  m.pair_t2 = (const int32_t*)(c.blob + h->off_pair_t2);
+  m.pair_row = (const int32_t*)(c.blob + h->off_pair_row);
+  m.t3 = (const int32_t*)(c.blob + h->off_t3);
   m.words = h->words;
   m.n_items = h->n_items;
+  m.ok = h->magic == GR_MASK_MAGIC && h->V == c.V && h->depth == c.depth;
   return m;
 }
 
@@ -103,14 +125,9 @@ __device__ __forceinline__ void row_children(const SelCtx& c, const MaskView& mv
   }
 }
 
-// Does this row get gathered (true) or streamed (false)?  Same decision in every kernel.
+// Does this row get gathered (true) or streamed (false)?
 __device__ __forceinline__ bool row_is_sparse(const SelCtx& c, int n_children) {
   return c.blob && c.step >= 1 && !(c.flags & GR_SELECT_FORCE_DENSE) && n_children <= kSparseMax;
-}
-
-// Token held by element slot e of chunk k of a dense row (or >= V when the slot is empty).
-__device__ __forceinline__ int dense_slot_token(const SelCtx& c, int k, int e) {
-  return c.vec4 ? 4 * (k + kChunksPerRow * (e >> 2)) + (e & 3) : k + kChunksPerRow * e;
 }
 
 __device__ __forceinline__ int lower_bound_i32(const int32_t* a, int n, int key) {
@@ -119,268 +136,492 @@ __device__ __forceinline__ int lower_bound_i32(const int32_t* a, int n, int key)
   return lo;
 }
 
-// exp(y) for y <= 0 in fp64, about 2 ulp: y = (64 n' + j) ln2/64 + r with |r| <= ln2/128,
-// exp(y) = 2^n' * 2^(j/64) * (1 + r + r^2/2 + ... + r^5/120).  `tab` holds 2^(j/64), j = 0..63.
-// Far cheaper than a general-purpose exp; its error is ~1e-16 relative, which the fp64 sum of a
-// row carries unchanged into the single fp32 rounding of lse.
-// The polynomial and range-reduction constants live in scalar registers (set up once per kernel):
-// left to itself the compiler re-materialises each 64-bit constant with vector moves inside every
-// conditional block that evaluates an exponential.
-struct ExpConsts { double inv_step, step_hi, step_lo, c5, c4, c3, c2; };
-__device__ __forceinline__ ExpConsts exp_consts() {
-  ExpConsts k = {92.33248261689366, -0x1.62e42fee00000p-7, -0x1.a39ef35793c76p-39, 1.0 / 120.0, 1.0 / 24.0, 1.0 / 6.0, 0.5};
-  asm volatile("" : "+s"(k.inv_step), "+s"(k.step_hi), "+s"(k.step_lo), "+s"(k.c5), "+s"(k.c4), "+s"(k.c3), "+s"(k.c2));
+// e^(x - ref) in fp64 for fp32 x <= ref (and not more than ~700 below it), about 1e-14 relative:
+//   t = (x - ref) * 64/ln2 = n + f with n = rint(t), |f| <= 1/2, both obtained from one addition of 1.5 * 2^52
+//   (whose low word then holds n); e^(x-ref) = 2^(n>>6) * 2^((n&63)/64) * 2^(f/64) with
+//   2^(f/64) - 1 = f (c1 + f (c2 + f (c3 + f c4))), c_k = (ln2/64)^k / k!  (truncation < 4e-14), the middle
+//   factor from a 64-entry table and the power of two added to the exponent field.  Eleven fp64
+//   operations; every one of them runs at the full fp64 rate.  The error is far below what the single
+//   fp32 rounding of lse = m + log S can see.
+// The constants live in scalar registers (set up once per kernel): left to itself the compiler
+// re-materialises each 64-bit literal with vector moves next to every use.
+struct ExpK { double c, magic, c1, c2, c3, c4; };
+__device__ __forceinline__ ExpK exp_consts() {
+  ExpK k = {0x1.71547652b82fep+6, 6755399441055744.0, 0x1.62e42fefa39efp-7, 0x1.ebfbdff82c58fp-15, 0x1.c6b08d704a0c0p-23,
+            0x1.3b2ab6fba4e77p-31};
+  asm volatile("" : "+s"(k.c), "+s"(k.magic), "+s"(k.c1), "+s"(k.c2), "+s"(k.c3), "+s"(k.c4));
   return k;
 }
-__device__ __forceinline__ double exp_nonpos(double y, const double* tab, const ExpConsts& k) {
-  const double nf = rint(y * k.inv_step);                      // 64 / ln 2
-  double r = fma(nf, k.step_hi, y);                            // ln2/64, high 32 bits (exact product)
-  r = fma(nf, k.step_lo, r);                                   // ln2/64, low part
-  double p = fma(r, k.c5, k.c4);
-  p = fma(p, r, k.c3);
-  p = fma(p, r, k.c2);
-  p = fma(p, r, 1.0);
-  p = p * r;
-  const int n = (int)nf;
-  const double t = tab[n & 63];
-  return ldexp(fma(t, p, t), n >> 6);
+__constant__ double c_exp_tab[64] = {
+    0x1.0000000000000p+0, 0x1.02c9a3e778061p+0, 0x1.059b0d3158574p+0, 0x1.0874518759bc8p+0,
+    0x1.0b5586cf9890fp+0, 0x1.0e3ec32d3d1a2p+0, 0x1.11301d0125b51p+0, 0x1.1429aaea92de0p+0,
+    0x1.172b83c7d517bp+0, 0x1.1a35beb6fcb75p+0, 0x1.1d4873168b9aap+0, 0x1.2063b88628cd6p+0,
+    0x1.2387a6e756238p+0, 0x1.26b4565e27cddp+0, 0x1.29e9df51fdee1p+0, 0x1.2d285a6e4030bp+0,
+    0x1.306fe0a31b715p+0, 0x1.33c08b26416ffp+0, 0x1.371a7373aa9cbp+0, 0x1.3a7db34e59ff7p+0,
+    0x1.3dea64c123422p+0, 0x1.4160a21f72e2ap+0, 0x1.44e086061892dp+0, 0x1.486a2b5c13cd0p+0,
+    0x1.4bfdad5362a27p+0, 0x1.4f9b2769d2ca7p+0, 0x1.5342b569d4f82p+0, 0x1.56f4736b527dap+0,
+    0x1.5ab07dd485429p+0, 0x1.5e76f15ad2148p+0, 0x1.6247eb03a5585p+0, 0x1.6623882552225p+0,
+    0x1.6a09e667f3bcdp+0, 0x1.6dfb23c651a2fp+0, 0x1.71f75e8ec5f74p+0, 0x1.75feb564267c9p+0,
+    0x1.7a11473eb0187p+0, 0x1.7e2f336cf4e62p+0, 0x1.82589994cce13p+0, 0x1.868d99b4492edp+0,
+    0x1.8ace5422aa0dbp+0, 0x1.8f1ae99157736p+0, 0x1.93737b0cdc5e5p+0, 0x1.97d829fde4e50p+0,
+    0x1.9c49182a3f090p+0, 0x1.a0c667b5de565p+0, 0x1.a5503b23e255dp+0, 0x1.a9e6b5579fdbfp+0,
+    0x1.ae89f995ad3adp+0, 0x1.b33a2b84f15fbp+0, 0x1.b7f76f2fb5e47p+0, 0x1.bcc1e904bc1d2p+0,
+    0x1.c199bdd85529cp+0, 0x1.c67f12e57d14bp+0, 0x1.cb720dcef9069p+0, 0x1.d072d4a07897cp+0,
+    0x1.d5818dcfba487p+0, 0x1.da9e603db3285p+0, 0x1.dfc97337b9b5fp+0, 0x1.e502ee78b3ff6p+0,
+    0x1.ea4afa2a490dap+0, 0x1.efa1bee615a27p+0, 0x1.f50765b6e4540p+0, 0x1.fa7c1819e90d8p+0};
+
+// rc = -(double)ref * k.c; x must be >= ref - 600 (callers clamp: what is cut off is below 1e-260 of the sum)
+__device__ __forceinline__ double exp_rel(float x, double rc, const double* tab, const ExpK& k) {
+  const double t = fma((double)x, k.c, rc);
+  const double u = t + k.magic;
+  const int n = __double2loint(u);
+  const double f = t - (u - k.magic);
+  double p = fma(f, k.c4, k.c3);
+  p = fma(p, f, k.c2);
+  p = fma(p, f, k.c1);
+  p = p * f;
+  const double tj = tab[n & 63];
+  const double r = fma(tj, p, tj);
+  return __hiloint2double(__double2hiint(r) + ((n >> 6) << 20), __double2loint(r));
 }
 
-template <int NWAVES>
-__device__ __forceinline__ float block_max(float v, float* s_red) {
+// max without the NaN-quieting instructions fmaxf() drags in (NaN inputs are outside the contract)
+__device__ __forceinline__ float max_raw(float a, float b) {
+  float r;
+  asm("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+  return r;
+}
+
+__device__ __forceinline__ uint64_t composite(float score, uint32_t flat) {
+  return ((uint64_t)gr_ordkey(score + 0.0f) << 32) | (uint64_t)(0xffffffffu - flat);     // (+0.0f: -0 and +0 are one score)
+}
+__device__ __forceinline__ float key_score(uint64_t key) { return gr_ordkey_inv((uint32_t)(key >> 32)); }
+
+// Monotone (non-increasing in the score) map of the scores in [bottom, top] onto the histogram bins, best score
+// in bin 0.  The scale follows the spread of the values at hand, so a wide spread (few valid children per row,
+// beams far apart) thins as well as a narrow one.
+struct BinMap { float top, scale; };
+__device__ __forceinline__ BinMap bin_map(float top, float bottom) {
+  const float range = top - bottom;
+  BinMap bm = {top, (range > 0.f && range < INFINITY) ? (float)(kHistBins - 1) / range : 0.f};
+  return bm;
+}
+__device__ __forceinline__ int key_bin(const BinMap& bm, float score) {
+  return (int)fminf(fmaxf((bm.top - score) * bm.scale, 0.f), (float)(kHistBins - 1));
+}
+
+// Data that one workgroup writes and another workgroup of the same launch reads (published survivors, row bias and
+// mode) moves with agent-scope relaxed atomics: the stores write through the XCD's L2 to memory and the loads
+// bypass it, so no workgroup has to write back and invalidate a whole L2 (what an agent-scope fence does on this
+// chip - measured at ~0.1 us per workgroup, serialised, when every workgroup executed one).
+template <class T>
+__device__ __forceinline__ void st_agent(T* p, T v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+template <class T>
+__device__ __forceinline__ T ld_agent(const T* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+
+// LDS of a workgroup
+struct Lds {
+  uint64_t* pool;      // [cap]
+  uint32_t* hist;      // [kHistBins]; also the queue of valid logits (float) of a thinly populated streamed row
+  uint32_t* mask;      // [words]
+  double* tab;         // [64]
+  float* redf;         // [kNW]
+  double* redd;        // [kNW]
+  uint32_t* redu;      // [kNW]
+  uint32_t* pn;        // pool length
+  int* thr;            // histogram threshold bin
+  uint32_t* flag;      // scratch word (overflow seen, last-arrival flag, list base)
+};
+
+__device__ __forceinline__ float block_max(float v, const Lds& L) {
   v = gr_wave_max(v);
   __syncthreads();
-  if (gr_lane() == 0) s_red[threadIdx.x >> 6] = v;
+  if (gr_lane() == 0) L.redf[threadIdx.x >> 6] = v;
   __syncthreads();
-  float r = s_red[0];
+  float r = L.redf[0];
 #pragma unroll
-  for (int i = 1; i < NWAVES; i++) r = fmaxf(r, s_red[i]);
+  for (int i = 1; i < kNW; i++) r = fmaxf(r, L.redf[i]);
   return r;
 }
-template <int NWAVES>
-__device__ __forceinline__ double block_sum(double v, double* s_red) {
+__device__ __forceinline__ float block_min(float v, const Lds& L) { return -block_max(-v, L); }
+__device__ __forceinline__ double block_sum(double v, const Lds& L) {
   v = gr_wave_sum(v);
   __syncthreads();
-  if (gr_lane() == 0) s_red[threadIdx.x >> 6] = v;
+  if (gr_lane() == 0) L.redd[threadIdx.x >> 6] = v;
   __syncthreads();
-  double r = s_red[0];
+  double r = L.redd[0];
 #pragma unroll
-  for (int i = 1; i < NWAVES; i++) r += s_red[i];
+  for (int i = 1; i < kNW; i++) r += L.redd[i];
   return r;
 }
-template <int NWAVES>
-__device__ __forceinline__ uint32_t block_sum_u32(uint32_t v, uint32_t* s_red) {
-  v = gr_wave_sum_u32(v);
-  __syncthreads();
-  if (gr_lane() == 0) s_red[threadIdx.x >> 6] = v;
-  __syncthreads();
-  uint32_t r = s_red[0];
+// exclusive prefix of v over the workgroup's threads (thread order), and the total
+__device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t* total, const Lds& L) {
+  const int lane = gr_lane(), wave = threadIdx.x >> 6;
+  uint32_t incl = v;
 #pragma unroll
-  for (int i = 1; i < NWAVES; i++) r += s_red[i];
-  return r;
+  for (int o = 1; o < 64; o <<= 1) {
+    const uint32_t t = __shfl_up(incl, o, 64);
+    if (lane >= o) incl += t;
+  }
+  __syncthreads();
+  if (lane == 63) L.redu[wave] = incl;
+  __syncthreads();
+  uint32_t base = 0, tot = 0;
+#pragma unroll
+  for (int i = 0; i < kNW; i++) { const uint32_t t = L.redu[i]; if (i < wave) base += t; tot += t; }
+  *total = tot;
+  return base + incl - v;
 }
 
-// ------------------------------------------------------------------------------------------------
-// Rows that are streamed in full.
-// ------------------------------------------------------------------------------------------------
-__device__ __forceinline__ void row_dense(const SelCtx& c, int owns_dead, int row) {
-  __shared__ uint32_t s_mask[kMaxMaskWords];
-  __shared__ float s_redf[kRowThreads / 64];
-  __shared__ double s_redd[kRowThreads / 64];
-  __shared__ float s_bias;
-  __shared__ double s_tab[64];
-  const int tid = threadIdx.x;
-  const float s_in = c.scores_in[row];
-  if (!(s_in > -INFINITY)) {
-    if (owns_dead && tid == 0) { c.row_mode[row] = ROW_DEAD; c.row_bias[row] = -INFINITY; c.row_top[row] = -INFINITY; }
-    return;                                        // the keys of a dead row are never read
+// Wave 0 only: smallest bin t with at least `want` entries in bins 0..t (bin 0 = best scores); the
+// last bin when there are fewer than `want` entries in total.
+__device__ __forceinline__ void hist_threshold(const uint32_t* s_hist, uint32_t want, int* s_thr) {
+  const int lane = threadIdx.x & 63;
+  constexpr int per = kHistBins / 64;
+  uint32_t local = 0;
+  for (int i = 0; i < per; i++) local += s_hist[lane * per + i];
+  uint32_t incl = local;   // inclusive prefix sum over lanes
+  for (int o = 1; o < 64; o <<= 1) {
+    uint32_t v = __shfl_up(incl, o, 64);
+    if (lane >= o) incl += v;
   }
-  const int V = c.V;
-  const int32_t* list = nullptr;
-  int n_list = 0;
-  MaskView mv;
-  if (c.blob) {
-    mv = mask_view(c.blob);
-    if (c.step >= 1) {
-      row_children(c, mv, row, &list, &n_list);
-      if (row_is_sparse(c, n_list)) return;      // a gathered row: rows_sparse owns it
-    }
+  const uint32_t tot = __shfl(incl, 63, 64);
+  const uint32_t below = incl - local;
+  if (tot < want) {
+    if (lane == 0) *s_thr = kHistBins - 1;
+  } else if (below < want && want <= incl) {
+    uint32_t acc = below;
+    int bin = lane * per;
+    for (;; bin++) { acc += s_hist[bin]; if (acc >= want) break; }
+    *s_thr = bin;
   }
-  if (tid < 64) s_tab[tid] = exp2((double)tid * (1.0 / 64.0));
-  const ExpConsts ek = exp_consts();
-  // ---- validity bits of the row in LDS
-  const int words = (V + 31) >> 5;
-  if (!c.blob) {
-    for (int i = tid; i < words; i += kRowThreads) s_mask[i] = 0xffffffffu;
-  } else if (c.step == 0) {
-    for (int i = tid; i < words; i += kRowThreads) s_mask[i] = mv.l0[i];
-  } else if (c.step == 1) {
-    const int t1 = c.prefix_in[(size_t)row * c.depth];
-    const bool ok = t1 >= 0 && t1 < V;
-    const uint32_t* src = mv.l1 + (size_t)(ok ? t1 : 0) * mv.words;
-    for (int i = tid; i < words; i += kRowThreads) s_mask[i] = ok ? src[i] : 0u;
-  } else {
-    // the last level has no dense mask: set the row's valid positions in an empty one
-    for (int i = tid; i < words; i += kRowThreads) s_mask[i] = 0u;
+}
+
+__device__ __forceinline__ void pool_push(const SelCtx& c, const Lds& L, uint64_t key) {
+  const uint32_t idx = atomicAdd(L.pn, 1u);
+  if (idx < (uint32_t)c.cap) L.pool[idx] = key;        // a longer pool is noticed at the next thinning point
+}
+
+// Thin the pool to the candidates that can still be among the W best of what this workgroup has seen:
+// histogram of the pool's scores below its best one, the bin in which the W-th best falls, everything
+// in worse bins dropped.  tau becomes the smallest surviving score once at least W candidates are known:
+// a later candidate below tau has W better ones ahead of it.  Called by the whole workgroup.
+// Returns false when the pool had overflowed (the request then takes the exact fallback).
+constexpr int kThinChunk = 8;                  // pool entries per thread and compaction round
+__device__ __forceinline__ bool pool_thin(const SelCtx& c, const Lds& L, float* tau) {
+  __syncthreads();
+  const uint32_t n_raw = *L.pn;
+  if (n_raw > (uint32_t)c.cap) return false;
+  const int n = (int)n_raw, tid = threadIdx.x;
+  if (n == 0) return true;
+  float top = -INFINITY, bottom = INFINITY;
+  for (int i = tid; i < n; i += kT) { const float s = key_score(L.pool[i]); top = fmaxf(top, s); bottom = fminf(bottom, s); }
+  top = block_max(top, L);
+  bottom = block_min(bottom, L);
+  const BinMap bm = bin_map(top, bottom);
+  for (int i = tid; i < kHistBins; i += kT) L.hist[i] = 0;
+  __syncthreads();
+  for (int i = tid; i < n; i += kT) atomicAdd(&L.hist[key_bin(bm, key_score(L.pool[i]))], 1u);
+  __syncthreads();
+  if (tid < 64) hist_threshold(L.hist, (uint32_t)c.W, L.thr);
+  if (tid == 0) *L.pn = 0;
+  __syncthreads();
+  const int thr = *L.thr;
+  float low = INFINITY;
+  // compaction in place, a slab of kThinChunk * kT entries at a time: a slab is in registers before anything is
+  // written, and what is kept lands at or below the slab's own start
+  for (int i0 = 0; i0 < n; i0 += kThinChunk * kT) {
+    uint64_t e[kThinChunk];
+#pragma unroll
+    for (int k = 0; k < kThinChunk; k++) { const int i = i0 + k * kT + tid; e[k] = (i < n) ? L.pool[i] : 0; }
     __syncthreads();
-    for (int i = tid; i < n_list; i += kRowThreads) { const int v = list[i]; atomicOr(&s_mask[v >> 5], 1u << (v & 31)); }
-  }
-  __syncthreads();
-
-  const float* x = c.logits + (size_t)row * V;
-  float lmax = -INFINITY;     // this thread's chunk: best valid logit
-  double S = 0.0;
-  float m;
-  if (c.vec4 && V <= kRegV4 * 4 * kRowThreads) {
-    // one HBM read: the row stays in registers
-    const int nv4 = V >> 2;
-    float4 xr[kRegV4];
-    uint32_t vb[kRegV4];
 #pragma unroll
-    for (int i = 0; i < kRegV4; i++) {
-      const int p = tid + i * kRowThreads;
-      xr[i] = make_float4(0.f, 0.f, 0.f, 0.f);
-      vb[i] = 0;
-      if (p < nv4) {
-        xr[i] = *(const float4*)(x + 4 * (size_t)p);
-        vb[i] = (s_mask[p >> 3] >> (4 * (p & 7))) & 0xfu;
-        if (4 * p + 3 >= V) vb[i] &= (1u << (V - 4 * p)) - 1u;
+    for (int k = 0; k < kThinChunk; k++)
+      if (i0 + k * kT + tid < n) {
+        const float s = key_score(e[k]);
+        if (key_bin(bm, s) <= thr) { L.pool[atomicAdd(L.pn, 1u)] = e[k]; low = fminf(low, s); }
       }
-    }
+    __syncthreads();
+  }
+  low = block_min(low, L);
+  if (n >= c.W) *tau = fmaxf(*tau, low);
+  return true;
+}
+
+// A conservative logit threshold for a row: fadd(bias, x) >= tau implies x >= the value returned.
+__device__ __forceinline__ float logit_threshold(float tau, float bias) {
+  if (!(tau > -INFINITY)) return -INFINITY;
+  const float d = __fsub_rn(tau, bias);
+  return d - (fabsf(tau) + fabsf(bias) + fabsf(d)) * 0x1p-21f;
+}
+
+// ------------------------------------------------------------------------------------------------
+// One streamed row, whole workgroup.  REG: the row (V % 4 == 0, V <= 8192, 16-byte aligned) is read
+// once and stays in registers; otherwise it is walked from memory (later passes hit in cache).
+// ------------------------------------------------------------------------------------------------
+template <bool REG>
+__device__ __forceinline__ void dense_row(const SelCtx& c, const MaskView& mv, const Lds& L, const ExpK& ek, int row, int w,
+                                          float s_in, const int32_t* list, int n_list, float* tau, bool* overflow) {
+  const int tid = threadIdx.x, V = c.V;
+  const float* x = c.logits + (size_t)row * V;
+  // ---- logits requested first, validity bits staged meanwhile
+  float4 xr[REG ? kRegV4 : 1];
+  const int nv4 = V >> 2;
+  if constexpr (REG) {
 #pragma unroll
     for (int i = 0; i < kRegV4; i++) {
-      if (vb[i] & 1u) lmax = fmaxf(lmax, xr[i].x);
-      if (vb[i] & 2u) lmax = fmaxf(lmax, xr[i].y);
-      if (vb[i] & 4u) lmax = fmaxf(lmax, xr[i].z);
-      if (vb[i] & 8u) lmax = fmaxf(lmax, xr[i].w);
+      const int p = tid + i * kT;
+      xr[i] = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
+      if (p < nv4) xr[i] = *(const float4*)(x + 4 * (size_t)p);
     }
-    m = block_max<kRowThreads / 64>(lmax, s_redf);
-    if (m > -INFINITY) {
-      const double md = (double)m;
+  }
+  const int words = c.words;
+  int n_valid_known = -1;                   // number of valid entries when the prefix state tells it
+  if (c.blob) {
+    if (c.step == 0) {
+      for (int i = tid; i < words; i += kT) L.mask[i] = mv.ok ? mv.l0[i] : 0u;
+    } else if (c.step == 1) {
+      const int t1 = c.prefix_in[(size_t)row * c.depth];
+      const bool ok = mv.ok && t1 >= 0 && t1 < V;
+      const uint32_t* src = mv.l1 + (size_t)(ok ? t1 : 0) * mv.words;
+      for (int i = tid; i < words; i += kT) L.mask[i] = ok ? src[i] : 0u;
+      n_valid_known = n_list;
+    } else {
+      // the last level has no dense mask: set the row's valid positions in an empty one
+      for (int i = tid; i < words; i += kT) L.mask[i] = 0u;
+      __syncthreads();
+      for (int i = tid; i < n_list; i += kT) { const int v = list[i]; atomicOr(&L.mask[v >> 5], 1u << (v & 31)); }
+      n_valid_known = n_list;
+    }
+    __syncthreads();
+  }
+  // ---- this thread's elements: token 4 * (tid + i * kT) + j in register mode, tid + k * kT otherwise.
+  // Invalid entries become -inf: they lose every max, add nothing to the sum and pass no threshold.
+  uint32_t vbits = 0xffffffffu;
+  if constexpr (REG) {
+    if (c.blob) {
+      vbits = 0;
 #pragma unroll
       for (int i = 0; i < kRegV4; i++) {
-        if (vb[i] & 1u) S += exp_nonpos((double)xr[i].x - md, s_tab, ek);
-        if (vb[i] & 2u) S += exp_nonpos((double)xr[i].y - md, s_tab, ek);
-        if (vb[i] & 4u) S += exp_nonpos((double)xr[i].z - md, s_tab, ek);
-        if (vb[i] & 8u) S += exp_nonpos((double)xr[i].w - md, s_tab, ek);
+        const int p = tid + i * kT;
+        if (p < nv4) vbits |= ((L.mask[p >> 3] >> (4 * (p & 7))) & 0xfu) << (4 * i);
       }
-    }
-  } else {
-    // general shape: two passes over the row (the second one hits in cache); same chunk layout
-    const int epc = c.epc;
-    for (int e = 0; e < epc; e++) {
-      const int v = dense_slot_token(c, tid, e);
-      if (v < V && ((s_mask[v >> 5] >> (v & 31)) & 1u)) lmax = fmaxf(lmax, x[v]);
-    }
-    m = block_max<kRowThreads / 64>(lmax, s_redf);
-    if (m > -INFINITY) {
-      const double md = (double)m;
-      for (int e = 0; e < epc; e++) {
-        const int v = dense_slot_token(c, tid, e);
-        if (v < V && ((s_mask[v >> 5] >> (v & 31)) & 1u)) S += exp_nonpos((double)x[v] - md, s_tab, ek);
+#pragma unroll
+      for (int i = 0; i < kRegV4; i++) {
+        if (!((vbits >> (4 * i)) & 1u)) xr[i].x = -INFINITY;
+        if (!((vbits >> (4 * i)) & 2u)) xr[i].y = -INFINITY;
+        if (!((vbits >> (4 * i)) & 4u)) xr[i].z = -INFINITY;
+        if (!((vbits >> (4 * i)) & 8u)) xr[i].w = -INFINITY;
       }
     }
   }
-  if (!(m > -INFINITY)) {
-    if (tid == 0) { c.row_mode[row] = ROW_DEAD; c.row_bias[row] = -INFINITY; c.row_top[row] = -INFINITY; }
+  auto mem_elem = [&](int v) { return (!c.blob || ((L.mask[v >> 5] >> (v & 31)) & 1u)) ? x[v] : -INFINITY; };
+  // f(x, token) over this thread's elements
+  auto for_each = [&](auto&& f) {
+    if constexpr (REG) {
+#pragma unroll
+      for (int i = 0; i < kRegV4; i++) {
+        const int v = 4 * (tid + i * kT);
+        f(xr[i].x, v); f(xr[i].y, v + 1); f(xr[i].z, v + 2); f(xr[i].w, v + 3);
+      }
+    } else {
+      for (int v = tid; v < V; v += kT) f(mem_elem(v), v);
+    }
+  };
+
+  // the request's shared threshold, one relaxed read for the whole workgroup (any older value is just as valid);
+  // published to the other threads by the barriers of the reductions below
+  if (tid == 0) *L.flag = __hip_atomic_load(&c.ctl[(size_t)(row / c.W) * kCtlWords + CTL_TAU], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  // ---- m = max over valid logits
+  float lmax = -INFINITY;
+  if constexpr (REG) {
+#pragma unroll
+    for (int i = 0; i < kRegV4; i++) lmax = max_raw(max_raw(max_raw(lmax, xr[i].x), max_raw(xr[i].y, xr[i].z)), xr[i].w);
+  } else {
+    for_each([&](float xv, int) { lmax = fmaxf(lmax, xv); });
+  }
+  if (w % kRowsPerWG == 0) GR_TL(c, 21);
+  const float m = block_max(lmax, L);
+  if (w % kRowsPerWG == 0) GR_TL(c, 22);
+  if (!(m > -INFINITY)) {                   // no valid token at all
+    if (tid == 0) { st_agent(&c.row_mode[row], (int32_t)ROW_DEAD); st_agent(&c.row_bias[row], -INFINITY); }
     return;
   }
-  S = block_sum<kRowThreads / 64>(S, s_redd);
-  if (tid == 0) {
-    const float lse = (float)((double)m + log(S));
-    const float bias = __fsub_rn(s_in, lse);
-    s_bias = bias;
-    c.row_bias[row] = bias;
-    c.row_mode[row] = ROW_DENSE;
-    c.row_top[row] = __fadd_rn(bias, m);
+  // ---- S = sum over valid exp(x - m) in fp64
+  const double rc = -(double)m * ek.c;
+  const float lo = m - 600.f;
+  double S = 0.0;
+  if (REG && n_valid_known >= 0 && n_valid_known <= kQueueMax) {
+    // thinly populated row: the valid logits are packed into a queue (thread order, so the sum is
+    // reproducible) and exponentiated with full lanes
+    float* q = (float*)L.hist;
+    uint32_t total;
+    const uint32_t base = block_excl_scan((uint32_t)__popc(vbits), &total, L);
+    uint32_t pos = base;
+    if constexpr (REG) {
+#pragma unroll
+      for (int i = 0; i < kRegV4; i++) {
+        if (((vbits >> (4 * i)) & 1u) && pos < (uint32_t)kQueueMax) q[pos++] = xr[i].x;
+        if (((vbits >> (4 * i)) & 2u) && pos < (uint32_t)kQueueMax) q[pos++] = xr[i].y;
+        if (((vbits >> (4 * i)) & 4u) && pos < (uint32_t)kQueueMax) q[pos++] = xr[i].z;
+        if (((vbits >> (4 * i)) & 8u) && pos < (uint32_t)kQueueMax) q[pos++] = xr[i].w;
+      }
+    }
+    __syncthreads();
+    const int nq = min((int)total, kQueueMax);
+    for (int i = tid; i < nq; i += kT) S += exp_rel(max_raw(q[i], lo), rc, L.tab, ek);
+  } else if constexpr (REG) {
+#pragma unroll
+    for (int i = 0; i < kRegV4; i++) {
+      S += exp_rel(max_raw(xr[i].x, lo), rc, L.tab, ek);
+      S += exp_rel(max_raw(xr[i].y, lo), rc, L.tab, ek);
+      S += exp_rel(max_raw(xr[i].z, lo), rc, L.tab, ek);
+      S += exp_rel(max_raw(xr[i].w, lo), rc, L.tab, ek);
+      // keep the four exponentials of a load together: hoisting the first halves of all 32 costs a hundred registers
+      asm volatile("" : "+v"(S)::"memory");
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  } else {
+    for_each([&](float xv, int) { if (xv > -INFINITY) S += exp_rel(fmaxf(xv, lo), rc, L.tab, ek); });
   }
-  __syncthreads();
-  c.chunk_key[(size_t)row * kChunksPerRow + tid] = (lmax > -INFINITY) ? __fadd_rn(s_bias, lmax) : -INFINITY;
+  const uint32_t pn0 = *L.pn;               // pool length before this row (read between barriers: no push is in flight)
+  if (w % kRowsPerWG == 0) GR_TL(c, 23);
+  S = block_sum(S, L);
+  if (w % kRowsPerWG == 0) GR_TL(c, 24);
+  const float lse = (float)((double)m + log(S));
+  const float bias = __fsub_rn(s_in, lse);
+  if (tid == 0) { st_agent(&c.row_bias[row], bias); st_agent(&c.row_mode[row], (int32_t)ROW_DENSE); }
+
+  // ---- candidates of the row that can still be among the W best
+  const uint32_t flat0 = (uint32_t)w * (uint32_t)V;
+  float t = *tau;
+  {
+    // what other workgroups of this request already know (read by one thread before the reductions above and
+    // handed out through LDS: every thread must act on the SAME value, the branches below contain barriers)
+    const uint32_t shared = *L.flag;
+    if (shared) t = fmaxf(t, gr_ordkey_inv(shared));
+    *tau = t;
+  }
+  bool by_histogram = !(t > -INFINITY);
+  if (!by_histogram) {
+    const float xt = logit_threshold(t, bias);
+    for_each([&](float xv, int v) {
+      if (xv >= xt) {
+        const float s = __fadd_rn(bias, xv);
+        if (s >= t) pool_push(c, L, composite(s, flat0 + (uint32_t)v));
+      }
+    });
+    __syncthreads();
+    if (*L.pn > (uint32_t)c.cap) {
+      // a threshold far below this row (another workgroup's, or one from much weaker rows) let too much through:
+      // take the row's pushes back and bound the row by its own W-th best instead
+      __syncthreads();
+      if (tid == 0) *L.pn = pn0;
+      if ((int)pn0 + c.W + kFlushSlack > c.cap) { if (!pool_thin(c, L, tau)) { *overflow = true; return; } }
+      by_histogram = true;
+    }
+  }
+  if (by_histogram) {
+    // histogram of this row's own candidates between its worst and its best one; the bin in which its W-th
+    // best falls bounds what the row can contribute
+    float lmin = INFINITY;
+    for_each([&](float xv, int) { if (xv > -INFINITY) lmin = fminf(lmin, xv); });
+    const BinMap bm = bin_map(__fadd_rn(bias, m), __fadd_rn(bias, block_min(lmin, L)));
+    for (int i = tid; i < kHistBins; i += kT) L.hist[i] = 0;
+    __syncthreads();
+    for_each([&](float xv, int) { if (xv > -INFINITY) atomicAdd(&L.hist[key_bin(bm, __fadd_rn(bias, xv))], 1u); });
+    __syncthreads();
+    if (tid < 64) hist_threshold(L.hist, (uint32_t)c.W, L.thr);
+    __syncthreads();
+    const int thr = *L.thr;
+    for_each([&](float xv, int v) {
+      if (xv > -INFINITY) {
+        const float s = __fadd_rn(bias, xv);
+        if (key_bin(bm, s) <= thr && s >= t) pool_push(c, L, composite(s, flat0 + (uint32_t)v));
+      }
+    });
+    __syncthreads();
+  }
+  const uint32_t pn = *L.pn;
+  if (w % kRowsPerWG == 0) GR_TL(c, 25);
+  if (pn > (uint32_t)c.cap) { *overflow = true; return; }
+  if ((int)pn >= c.cap / 2 || (!(*tau > -INFINITY) && (int)pn >= c.W)) {
+    if (!pool_thin(c, L, tau)) { *overflow = true; return; }
+    // let the other workgroups of the request profit at once
+    if (tid == 0 && *tau > -INFINITY) atomicMax(&c.ctl[(size_t)(row / c.W) * kCtlWords + CTL_TAU], gr_ordkey(*tau + 0.0f));
+  }
 }
 
 // ------------------------------------------------------------------------------------------------
-// Rows with few valid children: one wavefront each, gather only the valid logits (Section 6.1's
-// sparse form).  Chunk k of such a row = children k, k+64, k+128, ...
+// One gathered row (at most kSparseMax valid children), one wavefront: only the valid logits are read
+// (Section 6.1's sparse form).
 // ------------------------------------------------------------------------------------------------
-__device__ __forceinline__ void rows_sparse(const SelCtx& c, int group) {
-  __shared__ double s_tab[64];
-  if (threadIdx.x < 64) s_tab[threadIdx.x] = exp2((double)threadIdx.x * (1.0 / 64.0));
-  const ExpConsts ek = exp_consts();
-  __syncthreads();
-  const int row = group * (kRowThreads / 64) + (threadIdx.x >> 6);
-  const int lane = threadIdx.x & 63;
-  if (row >= c.B * c.W) return;
-  float* keys = c.chunk_key + (size_t)row * kChunksPerRow;
-  const float s_in = c.scores_in[row];
-  const MaskView mv = mask_view(c.blob);
-  const int32_t* list = nullptr;
-  int n = 0;
-  const bool live = s_in > -INFINITY;
-  if (live) {
-    row_children(c, mv, row, &list, &n);
-    if (!row_is_sparse(c, n)) return;          // a streamed row: row_dense owns it
-  }
-  if (!live || n == 0) {
-    if (lane == 0) { c.row_mode[row] = ROW_DEAD; c.row_bias[row] = -INFINITY; c.row_top[row] = -INFINITY; }
+__device__ __forceinline__ void sparse_row(const SelCtx& c, const Lds& L, const ExpK& ek, int row, int w, float s_in,
+                                           const int32_t* list, int n, float tau) {
+  const int lane = gr_lane();
+  if (n == 0) {
+    if (lane == 0) { st_agent(&c.row_mode[row], (int32_t)ROW_DEAD); st_agent(&c.row_bias[row], -INFINITY); }
     return;
   }
   const float* x = c.logits + (size_t)row * c.V;
   float xv[kSparseMax / 64];
+  int tok[kSparseMax / 64];
   float lmax = -INFINITY;
 #pragma unroll
   for (int k = 0; k < kSparseMax / 64; k++) {
     const int i = lane + 64 * k;
-    xv[k] = (i < n) ? x[list[i]] : -INFINITY;
+    tok[k] = (i < n) ? list[i] : -1;
+    xv[k] = (i < n) ? x[tok[k]] : -INFINITY;
     lmax = fmaxf(lmax, xv[k]);
   }
   const float m = gr_wave_max(lmax);
   double S = 0.0;
-  const double md = (double)m;
+  const double rc = -(double)m * ek.c;
+  const float lo = m - 600.f;
 #pragma unroll
   for (int k = 0; k < kSparseMax / 64; k++)
-    if (lane + 64 * k < n) S += exp_nonpos((double)xv[k] - md, s_tab, ek);
+    if (lane + 64 * k < n) S += exp_rel(fmaxf(xv[k], lo), rc, L.tab, ek);
   S = gr_wave_sum(S);
   const float lse = (float)((double)m + log(S));
   const float bias = __fsub_rn(s_in, lse);
-  if (lane == 0) { c.row_bias[row] = bias; c.row_mode[row] = ROW_SPARSE; c.row_top[row] = __fadd_rn(bias, m); }
-  keys[lane] = (lmax > -INFINITY) ? __fadd_rn(bias, lmax) : -INFINITY;     // a sparse row has kSparseKeys keys
-}
-
-// One launch for both kinds of row: the first n_dense_blocks workgroups stream one row each (those come
-// first because they run longest), the rest gather four sparse rows each.  Every row is looked at by
-// both kinds; the shared test row_is_sparse decides which of them owns it.
-__global__ void __launch_bounds__(kRowThreads) k_rows(SelCtx c, int owns_dead, int n_dense_blocks) {
-  if ((int)blockIdx.x < n_dense_blocks) row_dense(c, owns_dead, (int)blockIdx.x);
-  else rows_sparse(c, (int)blockIdx.x - n_dense_blocks);
+  if (lane == 0) { st_agent(&c.row_bias[row], bias); st_agent(&c.row_mode[row], (int32_t)ROW_SPARSE); }
+  const uint32_t flat0 = (uint32_t)w * (uint32_t)c.V;
+#pragma unroll
+  for (int k = 0; k < kSparseMax / 64; k++)
+    if (lane + 64 * k < n) {
+      const float s = __fadd_rn(bias, xv[k]);
+      if (!(tau > -INFINITY) || s >= tau) pool_push(c, L, composite(s, flat0 + (uint32_t)tok[k]));
+    }
 }
 
 // ------------------------------------------------------------------------------------------------
-// Per-request selection.
+// Exact fallback: MSB radix select of the W best composite keys over ALL candidates of the request
+// (slow, always correct; taken only when a pool overflowed).
 // ------------------------------------------------------------------------------------------------
 // Visit every finite candidate of request b.  f(score, flat, pred) is called wave-convergently
 // (pred = this lane holds a candidate).  Rows given by bit masks are strided by the whole
 // workgroup; rows given by child lists are taken one per wavefront.
 template <class F>
 __device__ __forceinline__ void for_each_candidate(const SelCtx& c, const MaskView& mv, int b, F&& f) {
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, nw = blockDim.x >> 6;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   if (!c.blob || c.step == 0) {
     for (int w = 0; w < c.W; w++) {
       const int row = b * c.W + w;
-      if (c.row_mode[row] == ROW_DEAD) continue;
-      const float bias = c.row_bias[row];
+      if (ld_agent(&c.row_mode[row]) == ROW_DEAD) continue;
+      const float bias = ld_agent(&c.row_bias[row]);
       const float* x = c.logits + (size_t)row * c.V;
       const uint32_t flat0 = (uint32_t)w * (uint32_t)c.V;
-      for (int v0 = 0; v0 < c.V; v0 += blockDim.x) {
+      for (int v0 = 0; v0 < c.V; v0 += kT) {
         const int v = v0 + threadIdx.x;
         const bool pred = v < c.V && (!c.blob || ((mv.l0[v >> 5] >> (v & 31)) & 1u));
         f(pred ? __fadd_rn(bias, x[v]) : 0.f, flat0 + v, pred);
       }
     }
   } else {
-    for (int w = wave; w < c.W; w += nw) {
+    for (int w = wave; w < c.W; w += kNW) {
       const int row = b * c.W + w;
-      if (c.row_mode[row] == ROW_DEAD) continue;
-      const float bias = c.row_bias[row];
+      if (ld_agent(&c.row_mode[row]) == ROW_DEAD) continue;
+      const float bias = ld_agent(&c.row_bias[row]);
       const float* x = c.logits + (size_t)row * c.V;
       const uint32_t flat0 = (uint32_t)w * (uint32_t)c.V;
       const int32_t* list;
@@ -396,22 +637,13 @@ __device__ __forceinline__ void for_each_candidate(const SelCtx& c, const MaskVi
   }
 }
 
-__device__ __forceinline__ uint64_t composite(float score, uint32_t flat) {
-  return ((uint64_t)gr_ordkey(score) << 32) | (uint64_t)(0xffffffffu - flat);
-}
-
-// Monotone (non-increasing in the score) bin index below the request's best chunk key.
-__device__ __forceinline__ int key_bin(float hi, float score) {
-  return (int)fminf(fmaxf((hi - score) * 64.0f, 0.f), (float)(kHistBins - 1));
-}
-
-// Exact MSB radix select of the W best composite keys over ALL candidates (slow, always correct).
-// Leaves the survivors in s_list and returns their number.
-__device__ int radix_select_all(const SelCtx& c, const MaskView& mv, int b, uint64_t* s_list, uint32_t* s_hist) {
+// Leaves the survivors (at most cap, at least min(W, number of candidates)) in the pool; returns their number.
+__device__ __forceinline__ int radix_select_all(const SelCtx& c, const MaskView& mv, int b, const Lds& L) {
   __shared__ uint64_t s_prefix;
   __shared__ uint32_t s_need, s_bin, s_cnt;
   __shared__ int s_all;
   const int tid = threadIdx.x, lane = tid & 63;
+  uint32_t* s_hist = L.hist;
   uint64_t prefix = 0;       // digits chosen so far (the top 64-shift bits of the W-th largest key)
   uint32_t need = (uint32_t)c.W;
   int shift = 64;            // number of key bits not yet fixed
@@ -420,7 +652,7 @@ __device__ int radix_select_all(const SelCtx& c, const MaskView& mv, int b, uint
     const int width = (pass < 5) ? 11 : 9;
     const int lo_shift = shift - width;
     const int nbins = 1 << width;
-    for (int i = tid; i < nbins; i += kSelThreads) s_hist[i] = 0;
+    for (int i = tid; i < nbins; i += kT) s_hist[i] = 0;
     __syncthreads();
     for_each_candidate(c, mv, b, [&](float score, uint32_t flat, bool pred) {
       const uint64_t k = composite(score, flat);
@@ -470,8 +702,8 @@ __device__ int radix_select_all(const SelCtx& c, const MaskView& mv, int b, uint
     prefix = s_prefix;
     need = s_need;
     shift = lo_shift;
-    // everything above the bin (W - need keys) plus the bin itself fits in LDS: stop refining
-    if ((uint32_t)c.W - need + s_bin <= (uint32_t)kListCap) break;
+    // everything above the bin (W - need keys) plus the bin itself fits in the pool: stop refining
+    if ((uint32_t)c.W - need + s_bin <= (uint32_t)c.cap) break;
   }
   if (tid == 0) s_cnt = 0;
   __syncthreads();
@@ -479,298 +711,109 @@ __device__ int radix_select_all(const SelCtx& c, const MaskView& mv, int b, uint
     const uint64_t k = composite(score, flat);
     if (pred && (take_all || (k >> shift) >= prefix)) {
       const uint32_t idx = atomicAdd(&s_cnt, 1u);
-      if (idx < (uint32_t)kListCap) s_list[idx] = k;
+      if (idx < (uint32_t)c.cap) L.pool[idx] = k;
     }
   });
   __syncthreads();
-  return min((int)s_cnt, kListCap);
+  return min((int)s_cnt, c.cap);
 }
 
-// Wave 0 only: smallest bin t with at least `want` entries in bins 0..t (bin 0 = best scores); the
-// last bin when there are fewer than `want` entries in total.
-__device__ __forceinline__ void hist_threshold(const uint32_t* s_hist, uint32_t want, int* s_thr) {
-  const int lane = threadIdx.x & 63;
-  constexpr int per = kHistBins / 64;
-  uint32_t local = 0;
-  for (int i = 0; i < per; i++) local += s_hist[lane * per + i];
-  uint32_t incl = local;   // inclusive prefix sum over lanes
-  for (int o = 1; o < 64; o <<= 1) {
-    uint32_t v = __shfl_up(incl, o, 64);
-    if (lane >= o) incl += v;
-  }
-  const uint32_t tot = __shfl(incl, 63, 64);
-  const uint32_t below = incl - local;
-  if (tot < want) {
-    if (lane == 0) *s_thr = kHistBins - 1;
-  } else if (below < want && want <= incl) {
-    uint32_t acc = below;
-    int bin = lane * per;
-    for (;; bin++) { acc += s_hist[bin]; if (acc >= want) break; }
-    *s_thr = bin;
-  }
-}
-
-__global__ void __launch_bounds__(kSelThreads) k_select(SelCtx c) {
-  extern __shared__ __attribute__((aligned(16))) char smem[];
-  uint64_t* s_list = (uint64_t*)smem;
-  uint32_t* s_hist = (uint32_t*)(smem + (size_t)kListCap * 8);
-  uint32_t* s_chunks = s_hist + kHistBins;
-  float* s_rbias = (float*)(s_chunks + kChunkCap);          // per beam row of the request: bias,
-  int32_t* s_rmode = (int32_t*)(s_rbias + kMaxW);            // mode,
-  int32_t* s_ra = s_rmode + kMaxW;                           // first token (step 1) or table range start (step 2),
-  int32_t* s_rb = s_ra + kMaxW;                              // table range end (step 2)
-  __shared__ float s_redf[kSelThreads / 64];
-  __shared__ uint16_t s_live[kMaxW];
-  __shared__ uint32_t s_n, s_nc, s_nlive;
-  __shared__ int s_thr;
-  const int b = blockIdx.x, tid = threadIdx.x;
-  constexpr int NW = kSelThreads / 64;
-  MaskView mv;
-  if (c.blob) mv = mask_view(c.blob);
-
-  if (tid == 0) { s_n = 0; s_nc = 0; s_nlive = 0; }
-  for (int i = tid; i < kHistBins; i += kSelThreads) s_hist[i] = 0;
-  __syncthreads();
-  // ---- the request's rows: what the rows kernels left, the live ones listed, the best candidate overall
-  float hi = -INFINITY;
-  for (int w = tid; w < c.W; w += kSelThreads) {
-    const size_t row = (size_t)b * c.W + w;
-    const int mode = c.row_mode[row];
-    s_rmode[w] = mode;
-    s_rbias[w] = c.row_bias[row];
-    int a = 0, bb = 0;
-    if (mode != ROW_DEAD) {
-      hi = fmaxf(hi, c.row_top[row]);
-      s_live[atomicAdd(&s_nlive, 1u)] = (uint16_t)w;
-      if (c.blob && c.step == 1) {
-        a = c.prefix_in[row * c.depth];
-      } else if (c.blob && c.step == 2) {
-        a = c.range_in[2 * row]; bb = c.range_in[2 * row + 1];
-        if (a < 0 || bb < a || (int64_t)bb > mv.n_items) { a = 0; bb = 0; }
-      }
-    }
-    s_ra[w] = a;
-    s_rb[w] = bb;
-  }
-  hi = block_max<NW>(hi, s_redf);          // (has the barriers that publish the row table)
-  const int nlive = (int)s_nlive;
-
-  // ---- threshold from the chunk keys of the live rows (the best candidate score of every 1/256th of a
-  // streamed row, every 1/64th of a gathered one).  Keys are read once and kept in registers for the
-  // second use when they fit (up to 256 live rows).
-  const float4* keys4 = (const float4*)(c.chunk_key + (size_t)b * c.W * kChunksPerRow);
-  constexpr int KR = 16;                   // float4 of keys per thread held in registers
-  const int ngroups = nlive * (kChunksPerRow / 4);
-  auto group_of = [&](int idx, int* w, int* g) {           // key group idx -> (row, group in row); false if it holds no keys
-    *w = s_live[idx / (kChunksPerRow / 4)];
-    *g = idx % (kChunksPerRow / 4);
-    return s_rmode[*w] == ROW_DENSE || *g < kSparseKeys / 4;
-  };
+// ------------------------------------------------------------------------------------------------
+// Last workgroup of a request: merge the published survivors, order the best W exactly, write the
+// new beam state, and leave the control words cleared.
+// ------------------------------------------------------------------------------------------------
+__device__ __forceinline__ void finalize_request(const SelCtx& c, const MaskView& mv, const Lds& L, int b) {
+  const int tid = threadIdx.x;
+  uint32_t* ctl = c.ctl + (size_t)b * kCtlWords;
+  const uint32_t n_list = __hip_atomic_load(&ctl[CTL_COUNT], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  const bool overflow = __hip_atomic_load(&ctl[CTL_OVERFLOW], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0;
+  const uint64_t* src = c.list + (size_t)b * c.G * c.flush_cap;
   int n = 0;
-  bool need_fallback = false;
-  if (hi > -INFINITY) {
-    float4 kq[KR];
+  bool fallback = overflow;
+  if (!fallback) {
+    if (n_list <= (uint32_t)c.cap) {
+      for (uint32_t i0 = 0; i0 < n_list; i0 += 8 * kT) {        // eight loads in flight per thread: they bypass the L2
+        uint64_t v[8];
 #pragma unroll
-    for (int i = 0; i < KR; i++) {
-      const int idx = tid + i * kSelThreads;
-      int w, g;
-      kq[i] = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
-      if (idx < ngroups && group_of(idx, &w, &g)) kq[i] = keys4[(size_t)w * (kChunksPerRow / 4) + g];
-    }
-    auto bin4 = [&](const float4& k, auto&& f) {
-      if (k.x > -INFINITY) f(0, key_bin(hi, k.x));
-      if (k.y > -INFINITY) f(1, key_bin(hi, k.y));
-      if (k.z > -INFINITY) f(2, key_bin(hi, k.z));
-      if (k.w > -INFINITY) f(3, key_bin(hi, k.w));
-    };
-    uint32_t kb[KR][2];                    // bins of the register-resident keys, 16 bits each (0xffff: no key)
+        for (int u = 0; u < 8; u++) { const uint32_t i = i0 + u * kT + tid; v[u] = (i < n_list) ? ld_agent(&src[i]) : 0; }
 #pragma unroll
-    for (int i = 0; i < KR; i++) {
-      kb[i][0] = 0xffffffffu; kb[i][1] = 0xffffffffu;
-      bin4(kq[i], [&](int j, int bin) {
-        atomicAdd(&s_hist[bin], 1u);
-        kb[i][j >> 1] = (j & 1) ? ((kb[i][j >> 1] & 0x0000ffffu) | ((uint32_t)bin << 16)) : ((kb[i][j >> 1] & 0xffff0000u) | (uint32_t)bin);
-      });
-    }
-    for (int idx = tid + KR * kSelThreads; idx < ngroups; idx += kSelThreads) {
-      int w, g;
-      if (group_of(idx, &w, &g)) bin4(keys4[(size_t)w * (kChunksPerRow / 4) + g], [&](int, int bin) { atomicAdd(&s_hist[bin], 1u); });
-    }
-    __syncthreads();
-    if (tid < 64) hist_threshold(s_hist, (uint32_t)c.W, &s_thr);
-    __syncthreads();
-    const int thr = s_thr;
-    // ---- chunks that reach the threshold
-    auto take = [&](int idx, const float4& k) {
-      int w, g;
-      group_of(idx, &w, &g);
-      bin4(k, [&](int j, int bin) {
-        if (bin <= thr) {
-          const uint32_t pos = atomicAdd(&s_nc, 1u);
-          if (pos < (uint32_t)kChunkCap) s_chunks[pos] = ((uint32_t)w << 8) | (uint32_t)(4 * g + j);
-        }
-      });
-    };
-#pragma unroll
-    for (int i = 0; i < KR; i++) {
-      const uint32_t b4[4] = {kb[i][0] & 0xffffu, kb[i][0] >> 16, kb[i][1] & 0xffffu, kb[i][1] >> 16};
-      const uint32_t thr_u = (uint32_t)thr;
-      if (b4[0] <= thr_u || b4[1] <= thr_u || b4[2] <= thr_u || b4[3] <= thr_u) {      // (0xffff never passes)
-        int w, g;
-        group_of(tid + i * kSelThreads, &w, &g);
-#pragma unroll
-        for (int j = 0; j < 4; j++)
-          if (b4[j] <= thr_u) {
-            const uint32_t pos = atomicAdd(&s_nc, 1u);
-            if (pos < (uint32_t)kChunkCap) s_chunks[pos] = ((uint32_t)w << 8) | (uint32_t)(4 * g + j);
-          }
+        for (int u = 0; u < 8; u++) { const uint32_t i = i0 + u * kT + tid; if (i < n_list) L.pool[i] = v[u]; }
       }
-    }
-    for (int idx = tid + KR * kSelThreads; idx < ngroups; idx += kSelThreads) {
-      int w, g;
-      if (group_of(idx, &w, &g)) take(idx, keys4[(size_t)w * (kChunksPerRow / 4) + g]);
-    }
-    __syncthreads();
-    const int nc = (int)s_nc;
-    if (nc > kChunkCap) {
-      need_fallback = true;
+      n = (int)n_list;
+      if (tid == 0) *L.pn = n_list;
     } else {
-      // ---- re-read only those chunks; keep their candidates that reach the threshold.  Four
-      // (chunk, element) slots per thread and round, all of their loads issued before any is used.
-      const int epc = max(c.epc, kSparseMax / kSparseKeys);
-      const int total = nc * epc;
-      constexpr int U = 8;
-      for (int base = 0; base < total; base += U * kSelThreads) {
-        int wv[U], tok[U];
-        float x[U];
-        uint32_t bits[U];
-        const int32_t* lst[U];
-        int nl[U];
-#pragma unroll
-        for (int q = 0; q < U; q++) {
-          const int idx = base + q * kSelThreads + tid;
-          tok[q] = -1; x[q] = 0.f; bits[q] = 0; lst[q] = nullptr; nl[q] = 0; wv[q] = 0;
-          if (idx < total) {
-            const uint32_t ent = s_chunks[idx / epc];
-            const int e = idx % epc;
-            const int w = (int)(ent >> 8), k = (int)(ent & 255u);
-            wv[q] = w;
-            const float* xrow = c.logits + ((size_t)b * c.W + w) * c.V;
-            if (s_rmode[w] == ROW_DENSE) {
-              const int t = (e < c.epc) ? dense_slot_token(c, k, e) : c.V;
-              if (t < c.V) {
-                tok[q] = t;
-                x[q] = xrow[t];
-                if (!c.blob) bits[q] = 1u;
-                else if (c.step == 0) bits[q] = (mv.l0[t >> 5] >> (t & 31)) & 1u;
-                else if (c.step == 1) {
-                  const int t1 = s_ra[w];
-                  bits[q] = (t1 >= 0 && t1 < c.V) ? ((mv.l1[(size_t)t1 * mv.words + (t >> 5)] >> (t & 31)) & 1u) : 0u;
-                } else { lst[q] = mv.t3 + s_ra[w]; nl[q] = s_rb[w] - s_ra[w]; }
-              }
-            } else {
-              // gathered row: chunk k = children k, k + 64, ...
-              const int32_t* list;
-              int nlist;
-              if (c.step == 1) {
-                const int t1 = s_ra[w];
-                const bool ok = t1 >= 0 && t1 < c.V;
-                const int p0 = ok ? mv.pair_off[t1] : 0, p1 = ok ? mv.pair_off[t1 + 1] : 0;
-                list = mv.pair_t2 + p0; nlist = p1 - p0;
-              } else { list = mv.t3 + s_ra[w]; nlist = s_rb[w] - s_ra[w]; }
-              const int i = k + kSparseKeys * e;
-              if (k < kSparseKeys && e < kSparseMax / kSparseKeys && i < nlist) {
-                const int t = list[i];
-                tok[q] = t;
-                x[q] = xrow[t];
-                bits[q] = 1u;
-              }
-            }
-          }
-        }
-#pragma unroll
-        for (int q = 0; q < U; q++) {
-          if (tok[q] < 0) continue;
-          bool ok = bits[q] != 0;
-          if (lst[q]) {                     // last level, streamed row: membership in the row's short child list
-            const int pos = lower_bound_i32(lst[q], nl[q], tok[q]);
-            ok = pos < nl[q] && lst[q][pos] == tok[q];
-          }
-          if (!ok) continue;
-          const float score = __fadd_rn(s_rbias[wv[q]], x[q]);
-          if (key_bin(hi, score) <= thr) {
-            const uint32_t pos = atomicAdd(&s_n, 1u);
-            if (pos < (uint32_t)kListCap) s_list[pos] = composite(score, (uint32_t)wv[q] * (uint32_t)c.V + (uint32_t)tok[q]);
-          }
-        }
+      // more published survivors than the pool holds: a histogram over all of them first
+      float top = -INFINITY, bottom = INFINITY;
+      for (uint32_t i = tid; i < n_list; i += kT) { const float sc = key_score(ld_agent(&src[i])); top = fmaxf(top, sc); bottom = fminf(bottom, sc); }
+      top = block_max(top, L);
+      bottom = block_min(bottom, L);
+      const BinMap bm = bin_map(top, bottom);
+      for (int i = tid; i < kHistBins; i += kT) L.hist[i] = 0;
+      if (tid == 0) *L.pn = 0;
+      __syncthreads();
+      for (uint32_t i = tid; i < n_list; i += kT) atomicAdd(&L.hist[key_bin(bm, key_score(ld_agent(&src[i])))], 1u);
+      __syncthreads();
+      if (tid < 64) hist_threshold(L.hist, (uint32_t)c.W, L.thr);
+      __syncthreads();
+      const int thr = *L.thr;
+      for (uint32_t i = tid; i < n_list; i += kT) {
+        const uint64_t k = ld_agent(&src[i]);
+        if (key_bin(bm, key_score(k)) <= thr) pool_push(c, L, k);
       }
       __syncthreads();
-      if (s_n > (uint32_t)kListCap) need_fallback = true;
-      n = min((int)s_n, kListCap);
-    }
-    if (need_fallback) n = radix_select_all(c, mv, b, s_list, s_hist);
-
-    // ---- many survivors (few chunks, or a coarse first threshold): refine on the scores themselves
-    if (n > 2 * c.W) {
-      uint64_t mine[kListCap / kSelThreads];
-      float top = -INFINITY;
-#pragma unroll
-      for (int k = 0; k < kListCap / kSelThreads; k++) {
-        const int i = tid + k * kSelThreads;
-        mine[k] = (i < n) ? s_list[i] : 0;
-        if (i < n) top = fmaxf(top, gr_ordkey_inv((uint32_t)(mine[k] >> 32)));
-      }
-      top = block_max<NW>(top, s_redf);
-      for (int i = tid; i < kHistBins; i += kSelThreads) s_hist[i] = 0;
-      if (tid == 0) s_n = 0;
-      __syncthreads();
-#pragma unroll
-      for (int k = 0; k < kListCap / kSelThreads; k++)
-        if (tid + k * kSelThreads < n) atomicAdd(&s_hist[key_bin(top, gr_ordkey_inv((uint32_t)(mine[k] >> 32)))], 1u);
-      __syncthreads();
-      if (tid < 64) hist_threshold(s_hist, (uint32_t)c.W, &s_thr);
-      __syncthreads();
-      const int thr2 = s_thr;
-#pragma unroll
-      for (int k = 0; k < kListCap / kSelThreads; k++)
-        if (tid + k * kSelThreads < n && key_bin(top, gr_ordkey_inv((uint32_t)(mine[k] >> 32))) <= thr2)
-          s_list[atomicAdd(&s_n, 1u)] = mine[k];
-      __syncthreads();
-      n = (int)s_n;
+      if (*L.pn > (uint32_t)c.cap) fallback = true;
+      n = (int)min(*L.pn, (uint32_t)c.cap);
     }
   }
+  for (int it = 0; it < 3 && !fallback && n > c.W + kFlushSlack; it++) {      // (each round zooms in on what the last one kept)
+    float tau = -INFINITY;
+    pool_thin(c, L, &tau);
+    n = (int)*L.pn;
+  }
+  if (fallback) n = radix_select_all(c, mv, b, L);
+  __syncthreads();
+  GR_TL(c, 14);
 
   // ---- order the survivors (descending composite key = score descending, flat index ascending)
+  uint64_t* s_list = L.pool;
   const uint64_t* s_sorted = s_list;
-  int n2 = 1;
-  while (n2 < n) n2 <<= 1;
-  if (n > 0 && n <= kSelThreads / 2) {
-    // few survivors (the usual case, about W of them): rank every key by counting the larger ones,
-    // kSelThreads / n threads per key, each scanning its share of the list.  Keys are distinct.
-    const int parts = kSelThreads / n;
-    const int i = tid / parts, part = tid % parts;
-    const int len = (n + parts - 1) / parts;
-    uint32_t* s_rank = s_hist;                            // (the histogram is no longer needed)
-    for (int k = tid; k < n; k += kSelThreads) s_rank[k] = 0;
-    __syncthreads();
-    if (i < n) {
-      const uint64_t mine = s_list[i];
-      const int j1 = min(n, (part + 1) * len);
-      uint32_t cnt = 0;
-      for (int j = part * len; j < j1; j++) cnt += s_list[j] > mine;
-      if (cnt) atomicAdd(&s_rank[i], cnt);
+  if (n > 0 && 2 * n <= c.cap && n <= 4 * kT) {
+    // few survivors (the usual case, about W of them): rank every key by counting the larger ones.  Keys are distinct.
+    uint64_t* s_out = s_list + c.cap / 2;
+    if (n <= kT) {
+      const int parts = kT / n;                              // threads per key, each scanning its share of the list
+      const int i = tid / parts, part = tid % parts;
+      const int len = (n + parts - 1) / parts;
+      uint32_t* s_rank = L.hist;
+      for (int k = tid; k < n; k += kT) s_rank[k] = 0;
+      __syncthreads();
+      if (i < n) {
+        const uint64_t mine = s_list[i];
+        const int j1 = min(n, (part + 1) * len);
+        uint32_t cnt = 0;
+        for (int j = part * len; j < j1; j++) cnt += s_list[j] > mine;
+        if (cnt) atomicAdd(&s_rank[i], cnt);
+      }
+      __syncthreads();
+      if (tid < n) s_out[s_rank[tid]] = s_list[tid];
+    } else {
+      for (int i = tid; i < n; i += kT) {
+        const uint64_t mine = s_list[i];
+        uint32_t cnt = 0;
+        for (int j = 0; j < n; j++) cnt += s_list[j] > mine;
+        s_out[cnt] = mine;
+      }
     }
-    __syncthreads();
-    uint64_t* s_out = s_list + kListCap / 2;             // n <= kSelThreads / 2 <= kListCap / 2: no overlap
-    if (tid < n) s_out[s_rank[tid]] = s_list[tid];
     s_sorted = s_out;
     __syncthreads();
-  } else {
-    for (int i = n + tid; i < n2; i += kSelThreads) s_list[i] = 0;   // 0 sorts after every real key
+  } else if (n > 0) {
+    int n2 = 1;
+    while (n2 < n) n2 <<= 1;                                 // n <= cap, and cap is a power of two
+    for (int i = n + tid; i < n2; i += kT) s_list[i] = 0;    // 0 sorts after every real key
     __syncthreads();
     for (int k = 2; k <= n2; k <<= 1) {
       for (int j = k >> 1; j > 0; j >>= 1) {
-        for (int i = tid; i < n2; i += kSelThreads) {
+        for (int i = tid; i < n2; i += kT) {
           const int ixj = i ^ j;
           if (ixj > i) {
             const uint64_t a = s_list[i], bb = s_list[ixj];
@@ -783,8 +826,9 @@ __global__ void __launch_bounds__(kSelThreads) k_select(SelCtx c) {
     }
   }
 
+  GR_TL(c, 15);
   // ---- write the new beam state, best first
-  for (int j = tid; j < c.W; j += kSelThreads) {
+  for (int j = tid; j < c.W; j += kT) {
     const size_t o = (size_t)b * c.W + j;
     int32_t* po = c.prefix_out + o * c.depth;
     for (int k = 0; k < c.depth; k++) po[k] = -1;
@@ -795,7 +839,7 @@ __global__ void __launch_bounds__(kSelThreads) k_select(SelCtx c) {
       const int parent = (int)(flat / (uint32_t)c.V), token = (int)(flat % (uint32_t)c.V);
       c.parent_out[o] = parent;
       c.token_out[o] = token;
-      c.scores_out[o] = gr_ordkey_inv((uint32_t)(key >> 32));
+      c.scores_out[o] = key_score(key);
       const size_t prow = (size_t)b * c.W + parent;
       for (int k = 0; k < c.step; k++) po[k] = c.prefix_in[prow * c.depth + k];
       po[c.step] = token;
@@ -824,18 +868,185 @@ __global__ void __launch_bounds__(kSelThreads) k_select(SelCtx c) {
     c.range_out[2 * o + 1] = r_hi;
     if (c.item_index_out) c.item_index_out[o] = item;
   }
+  // the control words are left as the next call expects them
+  if (tid < kCtlWords) ctl[tid] = 0;
+}
+
+template <bool REG>
+__global__ void __launch_bounds__(kT) __attribute__((amdgpu_waves_per_eu(4, 8))) k_item(SelCtx c) {
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  __shared__ float s_redf[kNW];
+  __shared__ double s_redd[kNW];
+  __shared__ uint32_t s_redu[kNW];
+  __shared__ uint32_t s_pn, s_flag;
+  __shared__ int s_thr;
+  Lds L;
+  L.pool = (uint64_t*)smem;
+  L.tab = (double*)(smem + (size_t)c.cap * 8);
+  L.hist = (uint32_t*)(L.tab + 64);
+  L.mask = L.hist + kHistBins;
+  L.redf = s_redf; L.redd = s_redd; L.redu = s_redu; L.pn = &s_pn; L.thr = &s_thr; L.flag = &s_flag;
+  const int tid = threadIdx.x, wave = tid >> 6;
+  const int b = (int)blockIdx.x / c.G, g = (int)blockIdx.x % c.G;
+  if (tid < 64) L.tab[tid] = c_exp_tab[tid];
+  if (tid == 0) { s_pn = 0; s_flag = 0; }
+  const ExpK ek = exp_consts();
+  MaskView mv;
+  mv.ok = true;
+  if (c.blob) mv = mask_view(c);
+  __syncthreads();
+
+  GR_TL(c, 0);
+  const int w0 = g * kRowsPerWG, w1 = min(c.W, w0 + kRowsPerWG);
+  float tau = -INFINITY;
+  bool overflow = false;
+  // ---- streamed rows first (the whole workgroup on one row), gathered rows remembered.  A workgroup whose
+  // pool has overflowed still walks all its rows: the exact fallback needs every row's bias.
+  uint32_t sparse_rows = 0;
+  for (int w = w0; w < w1; w++) {
+    const int row = b * c.W + w;
+    const float s_in = c.scores_in[row];
+    if (!(s_in > -INFINITY)) {
+      if (tid == 0) { st_agent(&c.row_mode[row], (int32_t)ROW_DEAD); st_agent(&c.row_bias[row], -INFINITY); }
+      continue;
+    }
+    const int32_t* list = nullptr;
+    int n_list = 0;
+    if (c.blob && c.step >= 1) {
+      if (mv.ok) row_children(c, mv, row, &list, &n_list);
+      if (row_is_sparse(c, n_list)) { sparse_rows |= 1u << (w - w0); continue; }
+    }
+    dense_row<REG>(c, mv, L, ek, row, w, s_in, list, n_list, &tau, &overflow);
+    GR_TL(c, 1 + (w - w0));
+  }
+  GR_TL(c, 9);
+  // ---- gathered rows, one per wavefront, kNW at a time
+  while (sparse_rows) {
+    // the wave-th set bit of the next kNW
+    uint32_t bits = sparse_rows;
+    int mine = -1;
+    for (int k = 0; k < kNW && bits; k++) {
+      const int i = __ffs(bits) - 1;
+      bits &= bits - 1;
+      if (k == wave) mine = i;
+    }
+    sparse_rows = bits;
+    if (mine >= 0) {
+      const int w = w0 + mine, row = b * c.W + w;
+      const int32_t* list = nullptr;
+      int n = 0;
+      if (mv.ok) row_children(c, mv, row, &list, &n);
+      sparse_row(c, L, ek, row, w, c.scores_in[row], list, n, tau);
+    }
+    __syncthreads();
+    const uint32_t pn = s_pn;
+    __syncthreads();                        // (a fast wavefront's next row must not push before every thread has read pn)
+    if (pn > (uint32_t)c.cap) overflow = true;
+    else if ((int)pn >= c.cap / 2 || (!(tau > -INFINITY) && (int)pn >= c.W)) {
+      if (!pool_thin(c, L, &tau)) overflow = true;
+      else if (tid == 0 && tau > -INFINITY) atomicMax(&c.ctl[(size_t)b * kCtlWords + CTL_TAU], gr_ordkey(tau + 0.0f));
+    }
+  }
+  // ---- publish what can still win
+  __syncthreads();
+  GR_TL(c, 10);
+  uint32_t* ctl = c.ctl + (size_t)b * kCtlWords;
+  for (int it = 0; it < 3 && !overflow && (int)s_pn > (it ? c.flush_cap : c.W); it++) {      // (each round zooms in on what the last one kept)
+    if (!pool_thin(c, L, &tau)) overflow = true;
+    __syncthreads();
+  }
+  __syncthreads();
+  uint32_t n_pub = 0;
+  if (!overflow) {
+    // drop what another workgroup's threshold has already ruled out (one read, handed out through LDS)
+    if (tid == 0) s_flag = __hip_atomic_load(&ctl[CTL_TAU], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __syncthreads();
+    const uint32_t shared = s_flag;
+    __syncthreads();
+    const uint32_t mine_key = (tau > -INFINITY) ? gr_ordkey(tau + 0.0f) : 0u;
+    const uint32_t floor_key = max(shared, mine_key);
+    const int n = (int)s_pn;
+    // count, reserve, write (thread order does not matter: the last workgroup orders by key)
+    uint32_t keep = 0;
+    for (int i = tid; i < n; i += kT) keep += (uint32_t)(L.pool[i] >> 32) >= floor_key;
+    uint32_t total;
+    uint32_t pos = block_excl_scan(keep, &total, L);
+    if (total > (uint32_t)c.flush_cap) {
+      overflow = true;
+    } else {
+      if (tid == 0) {
+        s_flag = total ? atomicAdd(&ctl[CTL_COUNT], total) : 0u;
+        if (mine_key > shared) atomicMax(&ctl[CTL_TAU], mine_key);
+      }
+      __syncthreads();
+      uint64_t* dst = c.list + (size_t)b * c.G * c.flush_cap + s_flag;
+      for (int i = tid; i < n; i += kT) {
+        const uint64_t k = L.pool[i];
+        if ((uint32_t)(k >> 32) >= floor_key) st_agent(&dst[pos++], k);
+      }
+      n_pub = total;
+    }
+  }
+  (void)n_pub;
+  if (overflow && tid == 0) atomicOr(&ctl[CTL_OVERFLOW], 1u);
+  // ---- ticket: the last workgroup of the request to get here finishes the request.  Every thread first waits
+  // until its write-through stores have been acknowledged; the barrier then orders them before the ticket.
+  GR_TL(c, 11);
+  asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+  __syncthreads();
+  GR_TL(c, 12);
+  if (tid == 0) s_flag = (atomicAdd(&ctl[CTL_TICKET], 1u) == (uint32_t)c.G - 1u) ? 1u : 0u;
+  __syncthreads();
+  GR_TL(c, 13);
+  if (!s_flag) return;
+  if (tid == 0) s_pn = 0;
+  __syncthreads();
+  finalize_request(c, mv, L, b);
+  GR_TL(c, 20);
+}
+
+__global__ void __launch_bounds__(256) k_item_init(uint32_t* ctl, int n) {
+  const int i = (int)blockIdx.x * 256 + (int)threadIdx.x;
+  if (i < n) ctl[i] = 0;
+}
+
+// Room for a thinned pool (about W) plus everything one row may add after being bounded by its own W-th best
+// (about W again) plus slack.
+int pool_cap(int W) {
+  int cap = 2048;
+  while (cap < 2 * W + 2 * kFlushSlack) cap <<= 1;
+  return cap;
+}
+
+struct SelLayout { size_t off_bias, off_mode, off_ctl, off_list, total; int G, cap, flush_cap; };
+SelLayout sel_layout(int B, int W) {
+  SelLayout l;
+  const size_t rows = (size_t)B * W;
+  l.G = (W + kRowsPerWG - 1) / kRowsPerWG;
+  l.cap = pool_cap(W);
+  l.flush_cap = W + kFlushSlack;
+  size_t o = 0;
+  l.off_ctl = o;  o += gr_align256((size_t)B * kCtlWords * 4);
+  l.off_bias = o; o += gr_align256(rows * 4);
+  l.off_mode = o; o += gr_align256(rows * 4);
+  l.off_list = o; o += gr_align256((size_t)B * l.G * l.flush_cap * 8);
+  l.total = o;
+  return l;
 }
 
 }  // namespace
 
+#ifdef GR_TIMELINE
+static unsigned long long* g_timeline = nullptr;
+extern "C" void gr_debug_set_timeline(void* p) { g_timeline = (unsigned long long*)p; }
+#endif
+
 extern "C" size_t gr_beam_select_workspace_bytes(int32_t B, int32_t W, int32_t V, int32_t depth) {
   if (B <= 0 || W <= 0 || V <= 0 || depth <= 0) return 0;
-  const size_t rows = (size_t)B * W;
-  return 3 * gr_align256(rows * 4) + gr_align256(rows * kChunksPerRow * 4);
+  return sel_layout(B, W).total;
 }
 
-extern "C" gr_status gr_beam_select(const gr_select_params* p, void* workspace, size_t workspace_bytes, void* stream_) {
-  hipStream_t stream = (hipStream_t)stream_;
+gr_status gr_select_launch(const gr_select_params* p, void* workspace, size_t workspace_bytes, hipStream_t stream) {
   if (!p) return GR_ERR_INVALID_ARG;
   if (p->B <= 0 || p->W <= 0 || p->V <= 0 || p->depth <= 0 || p->step < 0 || p->step >= p->depth) return GR_ERR_INVALID_ARG;
   if (!p->logits || !p->scores_in || !p->parent_out || !p->token_out || !p->scores_out || !p->prefix_out || !p->range_out)
@@ -843,32 +1054,49 @@ extern "C" gr_status gr_beam_select(const gr_select_params* p, void* workspace, 
   if (p->step > 0 && (!p->prefix_in || (p->mask && !p->range_in))) return GR_ERR_INVALID_ARG;
   if (p->prefix_in && p->prefix_in == p->prefix_out) return GR_ERR_INVALID_ARG;
   if (p->range_in && p->range_in == p->range_out) return GR_ERR_INVALID_ARG;
-  if (p->depth != 3 || p->W > 2048 || p->V > 32768 || (int64_t)p->W * p->V >= ((int64_t)1 << 31)) return GR_ERR_UNSUPPORTED;
+  if (p->depth != 3 || p->W > kMaxW || p->V > 32768 || (int64_t)p->W * p->V >= ((int64_t)1 << 31)) return GR_ERR_UNSUPPORTED;
   if ((int64_t)p->B * p->W >= ((int64_t)1 << 31)) return GR_ERR_UNSUPPORTED;
   if (!workspace || ((uintptr_t)workspace & 255)) return GR_ERR_INVALID_ARG;
-  if (workspace_bytes < gr_beam_select_workspace_bytes(p->B, p->W, p->V, p->depth)) return GR_ERR_WORKSPACE_TOO_SMALL;
+  const SelLayout lay = sel_layout(p->B, p->W);
+  if ((int64_t)p->B * lay.G >= ((int64_t)1 << 31)) return GR_ERR_UNSUPPORTED;
+  if (workspace_bytes < lay.total) return GR_ERR_WORKSPACE_TOO_SMALL;
 
   SelCtx c;
+#ifdef GR_TIMELINE
+  c.dbg = g_timeline;
+#endif
   c.B = p->B; c.W = p->W; c.V = p->V; c.depth = p->depth; c.step = p->step; c.flags = p->flags;
   c.vec4 = (p->V % 4 == 0) && (((uintptr_t)p->logits & 15) == 0);
-  c.epc = c.vec4 ? 4 * ((p->V / 4 + kChunksPerRow - 1) / kChunksPerRow) : (p->V + kChunksPerRow - 1) / kChunksPerRow;
+  c.G = lay.G; c.cap = lay.cap; c.flush_cap = lay.flush_cap;
+  c.words = (p->V + 31) / 32;
   c.blob = (const char*)p->mask;
   c.logits = p->logits; c.scores_in = p->scores_in; c.prefix_in = p->prefix_in; c.range_in = p->range_in;
   c.parent_out = p->parent_out; c.token_out = p->token_out; c.scores_out = p->scores_out;
   c.prefix_out = p->prefix_out; c.range_out = p->range_out; c.item_index_out = p->item_index_out;
-  const size_t rows = (size_t)p->B * p->W;
   char* ws = (char*)workspace;
-  c.row_bias = (float*)ws;                 ws += gr_align256(rows * 4);
-  c.row_mode = (int32_t*)ws;               ws += gr_align256(rows * 4);
-  c.row_top = (float*)ws;                  ws += gr_align256(rows * 4);
-  c.chunk_key = (float*)ws;
+  c.ctl = (uint32_t*)(ws + lay.off_ctl);
+  c.row_bias = (float*)(ws + lay.off_bias);
+  c.row_mode = (int32_t*)(ws + lay.off_mode);
+  c.list = (uint64_t*)(ws + lay.off_list);
 
-  const bool has_sparse = p->mask && p->step >= 1 && !(p->flags & GR_SELECT_FORCE_DENSE);
-  const size_t sparse_blocks = has_sparse ? (rows + kRowThreads / 64 - 1) / (kRowThreads / 64) : 0;
-  hipLaunchKernelGGL(k_rows, dim3((unsigned)(rows + sparse_blocks)), dim3(kRowThreads), 0, stream, c, has_sparse ? 0 : 1, (int)rows);
-  // more than 64 KB of LDS must be opted into (per device; cheap, so done on every call)
-  GR_HIP_TRY(hipFuncSetAttribute((const void*)k_select, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kSelLdsBytes));
-  hipLaunchKernelGGL(k_select, dim3(p->B), dim3(kSelThreads), kSelLdsBytes, stream, c);
+  if (!(p->flags & GR_SELECT_WORKSPACE_CLEAN)) {
+    const int n = p->B * kCtlWords;
+    hipLaunchKernelGGL(k_item_init, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, c.ctl, n);
+  }
+  const size_t lds = (size_t)c.cap * 8 + 64 * 8 + (size_t)kHistBins * 4 + (size_t)c.words * 4;
+  const bool reg = c.vec4 && p->V <= kRegV4 * 4 * kT;
+  const unsigned grid = (unsigned)((int64_t)p->B * lay.G);
+  if (reg) {
+    if (lds > 64 * 1024) GR_HIP_TRY(hipFuncSetAttribute((const void*)k_item<true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    hipLaunchKernelGGL(k_item<true>, dim3(grid), dim3(kT), lds, stream, c);
+  } else {
+    if (lds > 64 * 1024) GR_HIP_TRY(hipFuncSetAttribute((const void*)k_item<false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    hipLaunchKernelGGL(k_item<false>, dim3(grid), dim3(kT), lds, stream, c);
+  }
   GR_HIP_TRY(hipGetLastError());
   return GR_OK;
+}
+
+extern "C" gr_status gr_beam_select(const gr_select_params* p, void* workspace, size_t workspace_bytes, void* stream_) {
+  return gr_select_launch(p, workspace, workspace_bytes, (hipStream_t)stream_);
 }
