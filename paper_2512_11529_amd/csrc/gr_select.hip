@@ -32,9 +32,9 @@ namespace {
 
 constexpr int kT = 256;              // threads per workgroup
 constexpr int kNW = kT / 64;
-constexpr int kRowsPerWG = 8;        // beam rows a workgroup walks
+constexpr int kMaxRows = 16;         // most beam rows a workgroup walks (the host picks 8..16, see sel_layout)
 constexpr int kSparseMax = 256;      // rows with at most this many valid children are gathered, not streamed
-constexpr int kHistBins = 2048;
+constexpr int kHistBins = 1024;
 constexpr int kMaxMaskWords = 1024;  // V <= 32768
 constexpr int kRegV4 = 8;            // float4 per thread kept in registers (V <= 8192)
 constexpr int kQueueMax = kHistBins; // valid logits of a streamed row compacted before exponentiation (shares the histogram's LDS)
@@ -58,6 +58,7 @@ struct SelCtx {
 #endif
   int B, W, V, depth, step, flags;
   int vec4;                  // V % 4 == 0 and rows 16-byte aligned
+  int R;                     // beam rows per workgroup
   int G;                     // workgroups per request
   int cap;                   // candidates a workgroup's LDS pool holds
   int flush_cap;             // candidates a workgroup may publish
@@ -137,52 +138,37 @@ __device__ __forceinline__ int lower_bound_i32(const int32_t* a, int n, int key)
 }
 
 // e^(x - ref) in fp64 for fp32 x <= ref (and not more than ~700 below it), about 1e-14 relative:
-//   t = (x - ref) * 64/ln2 = n + f with n = rint(t), |f| <= 1/2, both obtained from one addition of 1.5 * 2^52
-//   (whose low word then holds n); e^(x-ref) = 2^(n>>6) * 2^((n&63)/64) * 2^(f/64) with
-//   2^(f/64) - 1 = f (c1 + f (c2 + f (c3 + f c4))), c_k = (ln2/64)^k / k!  (truncation < 4e-14), the middle
-//   factor from a 64-entry table and the power of two added to the exponent field.  Eleven fp64
-//   operations; every one of them runs at the full fp64 rate.  The error is far below what the single
-//   fp32 rounding of lse = m + log S can see.
+//   t = (x - ref) * 512/ln2 = n + f with n = rint(t), |f| <= 1/2, both from one addition of 1.5 * 2^52 (the sum's
+//   low word then holds n); e^(x-ref) = 2^(n>>9) * 2^((n&511)/512) * 2^(f/512) with
+//   2^(f/512) - 1 = f (c1 + f (c2 + f c3)), c_k = (ln2/512)^k / k!  (truncation < 1e-14), the middle factor from a
+//   512-entry table in LDS and the power of two added to the exponent field.  Ten fp64 and four integer operations;
+//   all run at the full rate.  The error is far below what the single fp32 rounding of lse = m + log S can see.
 // The constants live in scalar registers (set up once per kernel): left to itself the compiler
 // re-materialises each 64-bit literal with vector moves next to every use.
-struct ExpK { double c, magic, c1, c2, c3, c4; };
+constexpr int kExpTab = 512;
+struct ExpK { double c, magic, c1, c2, c3; };
 __device__ __forceinline__ ExpK exp_consts() {
-  ExpK k = {0x1.71547652b82fep+6, 6755399441055744.0, 0x1.62e42fefa39efp-7, 0x1.ebfbdff82c58fp-15, 0x1.c6b08d704a0c0p-23,
-            0x1.3b2ab6fba4e77p-31};
-  asm volatile("" : "+s"(k.c), "+s"(k.magic), "+s"(k.c1), "+s"(k.c2), "+s"(k.c3), "+s"(k.c4));
+  constexpr double a = 0x1.62e42fefa39efp-1 / 512.0;            // ln2 / 512
+  ExpK k = {512.0 * 0x1.71547652b82fep+0, 0x1.8p+52, a, a * a / 2.0, a * a * a / 6.0};
+  asm volatile("" : "+s"(k.c), "+s"(k.magic), "+s"(k.c1), "+s"(k.c2), "+s"(k.c3));
   return k;
 }
-__constant__ double c_exp_tab[64] = {
-    0x1.0000000000000p+0, 0x1.02c9a3e778061p+0, 0x1.059b0d3158574p+0, 0x1.0874518759bc8p+0,
-    0x1.0b5586cf9890fp+0, 0x1.0e3ec32d3d1a2p+0, 0x1.11301d0125b51p+0, 0x1.1429aaea92de0p+0,
-    0x1.172b83c7d517bp+0, 0x1.1a35beb6fcb75p+0, 0x1.1d4873168b9aap+0, 0x1.2063b88628cd6p+0,
-    0x1.2387a6e756238p+0, 0x1.26b4565e27cddp+0, 0x1.29e9df51fdee1p+0, 0x1.2d285a6e4030bp+0,
-    0x1.306fe0a31b715p+0, 0x1.33c08b26416ffp+0, 0x1.371a7373aa9cbp+0, 0x1.3a7db34e59ff7p+0,
-    0x1.3dea64c123422p+0, 0x1.4160a21f72e2ap+0, 0x1.44e086061892dp+0, 0x1.486a2b5c13cd0p+0,
-    0x1.4bfdad5362a27p+0, 0x1.4f9b2769d2ca7p+0, 0x1.5342b569d4f82p+0, 0x1.56f4736b527dap+0,
-    0x1.5ab07dd485429p+0, 0x1.5e76f15ad2148p+0, 0x1.6247eb03a5585p+0, 0x1.6623882552225p+0,
-    0x1.6a09e667f3bcdp+0, 0x1.6dfb23c651a2fp+0, 0x1.71f75e8ec5f74p+0, 0x1.75feb564267c9p+0,
-    0x1.7a11473eb0187p+0, 0x1.7e2f336cf4e62p+0, 0x1.82589994cce13p+0, 0x1.868d99b4492edp+0,
-    0x1.8ace5422aa0dbp+0, 0x1.8f1ae99157736p+0, 0x1.93737b0cdc5e5p+0, 0x1.97d829fde4e50p+0,
-    0x1.9c49182a3f090p+0, 0x1.a0c667b5de565p+0, 0x1.a5503b23e255dp+0, 0x1.a9e6b5579fdbfp+0,
-    0x1.ae89f995ad3adp+0, 0x1.b33a2b84f15fbp+0, 0x1.b7f76f2fb5e47p+0, 0x1.bcc1e904bc1d2p+0,
-    0x1.c199bdd85529cp+0, 0x1.c67f12e57d14bp+0, 0x1.cb720dcef9069p+0, 0x1.d072d4a07897cp+0,
-    0x1.d5818dcfba487p+0, 0x1.da9e603db3285p+0, 0x1.dfc97337b9b5fp+0, 0x1.e502ee78b3ff6p+0,
-    0x1.ea4afa2a490dap+0, 0x1.efa1bee615a27p+0, 0x1.f50765b6e4540p+0, 0x1.fa7c1819e90d8p+0};
-
+// The table 2^(j/512), j = 0..511, computed by the workgroup itself (two exp2 per thread).
+__device__ __forceinline__ void exp_table_init(double* tab) {
+  for (int j = threadIdx.x; j < kExpTab; j += blockDim.x) tab[j] = exp2((double)j * (1.0 / kExpTab));
+}
 // rc = -(double)ref * k.c; x must be >= ref - 600 (callers clamp: what is cut off is below 1e-260 of the sum)
 __device__ __forceinline__ double exp_rel(float x, double rc, const double* tab, const ExpK& k) {
   const double t = fma((double)x, k.c, rc);
   const double u = t + k.magic;
   const int n = __double2loint(u);
   const double f = t - (u - k.magic);
-  double p = fma(f, k.c4, k.c3);
-  p = fma(p, f, k.c2);
+  double p = fma(f, k.c3, k.c2);
   p = fma(p, f, k.c1);
   p = p * f;
-  const double tj = tab[n & 63];
+  const double tj = tab[n & (kExpTab - 1)];
   const double r = fma(tj, p, tj);
-  return __hiloint2double(__double2hiint(r) + ((n >> 6) << 20), __double2loint(r));
+  return __hiloint2double(__double2hiint(r) + ((n >> 9) << 20), __double2loint(r));
 }
 
 // max without the NaN-quieting instructions fmaxf() drags in (NaN inputs are outside the contract)
@@ -224,34 +210,42 @@ struct Lds {
   uint64_t* pool;      // [cap]
   uint32_t* hist;      // [kHistBins]; also the queue of valid logits (float) of a thinly populated streamed row
   uint32_t* mask;      // [words]
-  double* tab;         // [64]
-  float* redf;         // [kNW]
-  double* redd;        // [kNW]
-  uint32_t* redu;      // [kNW]
+  float* next;         // [kRegV4 * kT * 4] staging area of the next streamed row (register-resident kernels)
+  double* tab;         // [kExpTab]
+  float* redf;         // [2 * kNW]  two slot sets per kind of reduction, see block_max
+  double* redd;        // [2 * kNW]
+  uint32_t* redu;      // [2 * kNW]
+  mutable int par;     // reductions made so far (same in every thread)
   uint32_t* pn;        // pool length
   int* thr;            // histogram threshold bin
   uint32_t* flag;      // scratch word (overflow seen, last-arrival flag, list base)
 };
 
+// Workgroup reductions with ONE barrier each: the per-wavefront partials go to one of two slot sets, used
+// alternately (every thread makes the same sequence of calls), so a wavefront that is already writing the
+// next reduction's partials cannot disturb a slower one that still reads this one's; the set after that is
+// only written behind the next reduction's barrier.
 __device__ __forceinline__ float block_max(float v, const Lds& L) {
   v = gr_wave_max(v);
+  float* slot = L.redf + (L.par & 1) * kNW;
+  L.par++;
+  if (gr_lane() == 0) slot[threadIdx.x >> 6] = v;
   __syncthreads();
-  if (gr_lane() == 0) L.redf[threadIdx.x >> 6] = v;
-  __syncthreads();
-  float r = L.redf[0];
+  float r = slot[0];
 #pragma unroll
-  for (int i = 1; i < kNW; i++) r = fmaxf(r, L.redf[i]);
+  for (int i = 1; i < kNW; i++) r = fmaxf(r, slot[i]);
   return r;
 }
 __device__ __forceinline__ float block_min(float v, const Lds& L) { return -block_max(-v, L); }
 __device__ __forceinline__ double block_sum(double v, const Lds& L) {
   v = gr_wave_sum(v);
+  double* slot = L.redd + (L.par & 1) * kNW;
+  L.par++;
+  if (gr_lane() == 0) slot[threadIdx.x >> 6] = v;
   __syncthreads();
-  if (gr_lane() == 0) L.redd[threadIdx.x >> 6] = v;
-  __syncthreads();
-  double r = L.redd[0];
+  double r = slot[0];
 #pragma unroll
-  for (int i = 1; i < kNW; i++) r += L.redd[i];
+  for (int i = 1; i < kNW; i++) r += slot[i];
   return r;
 }
 // exclusive prefix of v over the workgroup's threads (thread order), and the total
@@ -263,19 +257,20 @@ __device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t* total,
     const uint32_t t = __shfl_up(incl, o, 64);
     if (lane >= o) incl += t;
   }
-  __syncthreads();
-  if (lane == 63) L.redu[wave] = incl;
+  uint32_t* slot = L.redu + (L.par & 1) * kNW;
+  L.par++;
+  if (lane == 63) slot[wave] = incl;
   __syncthreads();
   uint32_t base = 0, tot = 0;
 #pragma unroll
-  for (int i = 0; i < kNW; i++) { const uint32_t t = L.redu[i]; if (i < wave) base += t; tot += t; }
+  for (int i = 0; i < kNW; i++) { const uint32_t t = slot[i]; if (i < wave) base += t; tot += t; }
   *total = tot;
   return base + incl - v;
 }
 
 // Wave 0 only: smallest bin t with at least `want` entries in bins 0..t (bin 0 = best scores); the
 // last bin when there are fewer than `want` entries in total.
-__device__ __forceinline__ void hist_threshold(const uint32_t* s_hist, uint32_t want, int* s_thr) {
+__device__ __forceinline__ void hist_threshold(const uint32_t* s_hist, uint32_t want, int* s_thr, uint32_t* s_tot = nullptr) {
   const int lane = threadIdx.x & 63;
   constexpr int per = kHistBins / 64;
   uint32_t local = 0;
@@ -287,6 +282,7 @@ __device__ __forceinline__ void hist_threshold(const uint32_t* s_hist, uint32_t 
   }
   const uint32_t tot = __shfl(incl, 63, 64);
   const uint32_t below = incl - local;
+  if (s_tot && lane == 0) *s_tot = tot;
   if (tot < want) {
     if (lane == 0) *s_thr = kHistBins - 1;
   } else if (below < want && want <= incl) {
@@ -440,9 +436,9 @@ __device__ __forceinline__ void dense_row(const SelCtx& c, const MaskView& mv, c
   } else {
     for_each([&](float xv, int) { lmax = fmaxf(lmax, xv); });
   }
-  if (w % kRowsPerWG == 0) GR_TL(c, 21);
+  if (w % c.R == 1) GR_TL(c, 21);
   const float m = block_max(lmax, L);
-  if (w % kRowsPerWG == 0) GR_TL(c, 22);
+  if (w % c.R == 1) GR_TL(c, 22);
   if (!(m > -INFINITY)) {                   // no valid token at all
     if (tid == 0) { st_agent(&c.row_mode[row], (int32_t)ROW_DEAD); st_agent(&c.row_bias[row], -INFINITY); }
     return;
@@ -485,9 +481,9 @@ __device__ __forceinline__ void dense_row(const SelCtx& c, const MaskView& mv, c
     for_each([&](float xv, int) { if (xv > -INFINITY) S += exp_rel(fmaxf(xv, lo), rc, L.tab, ek); });
   }
   const uint32_t pn0 = *L.pn;               // pool length before this row (read between barriers: no push is in flight)
-  if (w % kRowsPerWG == 0) GR_TL(c, 23);
+  if (w % c.R == 1) GR_TL(c, 23);
   S = block_sum(S, L);
-  if (w % kRowsPerWG == 0) GR_TL(c, 24);
+  if (w % c.R == 1) GR_TL(c, 24);
   const float lse = (float)((double)m + log(S));
   const float bias = __fsub_rn(s_in, lse);
   if (tid == 0) { st_agent(&c.row_bias[row], bias); st_agent(&c.row_mode[row], (int32_t)ROW_DENSE); }
@@ -543,8 +539,277 @@ __device__ __forceinline__ void dense_row(const SelCtx& c, const MaskView& mv, c
     __syncthreads();
   }
   const uint32_t pn = *L.pn;
-  if (w % kRowsPerWG == 0) GR_TL(c, 25);
+  if (w % c.R == 1) GR_TL(c, 25);
   if (pn > (uint32_t)c.cap) { *overflow = true; return; }
+  if ((int)pn >= c.cap / 2 || (!(*tau > -INFINITY) && (int)pn >= c.W)) {
+    if (!pool_thin(c, L, tau)) { *overflow = true; return; }
+    // let the other workgroups of the request profit at once
+    if (tid == 0 && *tau > -INFINITY) atomicMax(&c.ctl[(size_t)(row / c.W) * kCtlWords + CTL_TAU], gr_ordkey(*tau + 0.0f));
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Streamed rows, register-resident form (V % 4 == 0, V <= 8192, rows 16-byte aligned, W <= kT): the workgroup's
+// rows are classified by eight threads at once, the NEXT streamed row's logits and mask words are requested
+// before the current row is worked on (two register sets), the validity bits come straight from the mask row in
+// memory (no LDS staging, no barrier), and a row whose best candidate cannot reach tau costs a thread one compare.
+// ------------------------------------------------------------------------------------------------
+// The register-resident kernel is compiled once per kind of call (MODE 0: no mask; 1, 2, 3: masked levels 0, 1, 2)
+// so that none of them carries the others' branches and pointers; MODE -1 decides at run time.
+template <int MODE> __device__ __forceinline__ bool is_masked(const SelCtx& c) { if constexpr (MODE < 0) return c.blob != nullptr; else return MODE != 0; }
+template <int MODE> __device__ __forceinline__ int level_of(const SelCtx& c) { if constexpr (MODE <= 0) return c.step; else return MODE - 1; }
+
+struct RowMeta {           // one per row of the workgroup, in LDS
+  float s_in;
+  int cls;                 // ROW_DEAD / ROW_DENSE / ROW_SPARSE
+  int n_list;              // valid children (levels 1, 2), else -1
+  int t1;                  // first token of the prefix (level 1), else -1
+  const int32_t* list;     // sorted valid children (levels 1, 2)
+};
+struct RowRegs {
+  float4 x[kRegV4];        // tokens 4 * (tid + i * kT) .. + 3
+  uint32_t mw[kRegV4];     // the mask words that hold this thread's validity nibbles (levels 0 and 1)
+};
+
+// Request the next streamed row: its logits go straight from memory into the workgroup's LDS staging area
+// (LDS-direct loads: no registers are tied up while the current row is worked on; lane l of a wavefront's i-th
+// load lands at slot (i * kT + tid) * 16 bytes), its mask words into eight registers.
+template <int MODE>
+__device__ __forceinline__ void row_prefetch(const SelCtx& c, const MaskView& mv, const Lds& L, int row, const RowMeta& rm, uint32_t (&mw)[kRegV4]) {
+  const int tid = threadIdx.x, nv4 = c.V >> 2;
+  const float* x = c.logits + (size_t)row * c.V;
+#pragma unroll
+  for (int i = 0; i < kRegV4; i++) {
+    const int p = tid + i * kT;
+    if (p < nv4)
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(x + 4 * (size_t)p),
+                                       (__attribute__((address_space(3))) void*)(L.next + (size_t)(i * kT + (tid & ~63)) * 4), 16, 0, 0);
+  }
+  if (is_masked<MODE>(c)) {
+    const int step = level_of<MODE>(c);
+    const uint32_t* mrow = nullptr;
+    if (step == 0) mrow = mv.ok ? mv.l0 : nullptr;
+    else if (step == 1) mrow = (mv.ok && rm.t1 >= 0 && rm.t1 < c.V) ? mv.l1 + (size_t)rm.t1 * mv.words : nullptr;
+#pragma unroll
+    for (int i = 0; i < kRegV4; i++) {
+      const int wi = (tid >> 3) + 32 * i;          // float4 p = tid + i * kT has its nibble in word p >> 3
+      mw[i] = (mrow && wi < c.words) ? mrow[wi] : 0u;
+    }
+  }
+}
+// Take the staged row into registers (every thread reads back exactly what its own loads brought in).
+__device__ __forceinline__ void row_take(const SelCtx& c, const Lds& L, RowRegs& R) {
+  const int tid = threadIdx.x, nv4 = c.V >> 2;
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#pragma unroll
+  for (int i = 0; i < kRegV4; i++) {
+    const int p = tid + i * kT;
+    const float4 v = *(const float4*)(L.next + (size_t)(i * kT + tid) * 4);
+    R.x[i] = (p < nv4) ? v : make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
+  }
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");      // the staging area may be overwritten by this thread's next request
+}
+
+template <int MODE>
+__device__ __forceinline__ void row_process(const SelCtx& c, const MaskView& mv, const Lds& L, const ExpK& ek, int row, int w,
+                                            const RowMeta& rm, RowRegs& R, uint32_t shared_tau, float* tau, bool* overflow) {
+  const int tid = threadIdx.x, V = c.V, nv4 = V >> 2;
+  const bool masked = is_masked<MODE>(c);
+  const int step = level_of<MODE>(c);
+  float4(&xr)[kRegV4] = R.x;
+  // ---- validity bits: bit 4 i + j <-> token 4 (tid + i kT) + j.  Invalid entries become -inf: they lose every
+  // max, add nothing to the sum and pass no threshold.
+  uint32_t vbits = 0;
+  if (!masked) {
+#pragma unroll
+    for (int i = 0; i < kRegV4; i++) if (tid + i * kT < nv4) vbits |= 0xfu << (4 * i);
+  } else {
+#pragma unroll
+    for (int i = 0; i < kRegV4; i++) vbits |= ((R.mw[i] >> (4 * (tid & 7))) & 0xfu) << (4 * i);
+    if (step == 2) {
+      // the last level has no dense mask: the row's few valid positions are set one by one (Section 6.1's sparse form
+      // applied to an existing mask)
+      if (rm.n_list <= 64) {
+        // (scalar loads: they do not queue up behind the next row's vector loads)
+        const int32_t* lp = (const int32_t*)(((uint64_t)__builtin_amdgcn_readfirstlane((int)((uint64_t)rm.list >> 32)) << 32) |
+                                             (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(uint64_t)rm.list));
+        const int nl = __builtin_amdgcn_readfirstlane(rm.n_list);
+        for (int e = 0; e < nl; e++) {
+          const int t = lp[e];
+          if (((t >> 2) & (kT - 1)) == tid) vbits |= 1u << (4 * (t >> 10) + (t & 3));
+        }
+      } else {
+        for (int i = tid; i < c.words; i += kT) L.mask[i] = 0u;
+        __syncthreads();
+        for (int i = tid; i < rm.n_list; i += kT) { const int v = rm.list[i]; atomicOr(&L.mask[v >> 5], 1u << (v & 31)); }
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < kRegV4; i++) {
+          const int p = tid + i * kT;
+          if (p < nv4) vbits |= ((L.mask[p >> 3] >> (4 * (p & 7))) & 0xfu) << (4 * i);
+        }
+        __syncthreads();
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < kRegV4; i++) {
+      if (!((vbits >> (4 * i)) & 1u)) xr[i].x = -INFINITY;
+      if (!((vbits >> (4 * i)) & 2u)) xr[i].y = -INFINITY;
+      if (!((vbits >> (4 * i)) & 4u)) xr[i].z = -INFINITY;
+      if (!((vbits >> (4 * i)) & 8u)) xr[i].w = -INFINITY;
+    }
+  }
+  // ---- m = max over valid logits
+  float lmax = -INFINITY;
+#pragma unroll
+  for (int i = 0; i < kRegV4; i++) lmax = max_raw(max_raw(max_raw(lmax, xr[i].x), max_raw(xr[i].y, xr[i].z)), xr[i].w);
+  if (w % c.R == 1) GR_TL(c, 21);
+  const float m = block_max(lmax, L);
+  if (w % c.R == 1) GR_TL(c, 22);
+  if (!(m > -INFINITY)) {                   // no valid token at all
+    if (tid == 0) { st_agent(&c.row_mode[row], (int32_t)ROW_DEAD); st_agent(&c.row_bias[row], -INFINITY); }
+    return;
+  }
+  // ---- S = sum over valid exp(x - m) in fp64
+  const double rc = -(double)m * ek.c;
+  const float lo = m - 600.f;
+  double S = 0.0;
+  const uint32_t pn0 = *L.pn;               // pool length before this row (read between barriers: no push is in flight)
+  if (masked && step >= 1 && rm.n_list <= kQueueMax) {
+    // thinly populated row: the valid logits are packed into a queue (thread order, so the sum is
+    // reproducible) and exponentiated with full lanes
+    float* q = (float*)L.hist;
+    uint32_t total;
+    uint32_t pos = block_excl_scan((uint32_t)__popc(vbits), &total, L);
+#pragma unroll
+    for (int i = 0; i < kRegV4; i++) {
+      if (((vbits >> (4 * i)) & 1u) && pos < (uint32_t)kQueueMax) q[pos++] = xr[i].x;
+      if (((vbits >> (4 * i)) & 2u) && pos < (uint32_t)kQueueMax) q[pos++] = xr[i].y;
+      if (((vbits >> (4 * i)) & 4u) && pos < (uint32_t)kQueueMax) q[pos++] = xr[i].z;
+      if (((vbits >> (4 * i)) & 8u) && pos < (uint32_t)kQueueMax) q[pos++] = xr[i].w;
+    }
+    __syncthreads();
+    const int nq = min((int)total, kQueueMax);
+    for (int i = tid; i < nq; i += kT) S += exp_rel(max_raw(q[i], lo), rc, L.tab, ek);
+  } else {
+#pragma unroll
+    for (int i = 0; i < kRegV4; i++) {
+      S += exp_rel(max_raw(xr[i].x, lo), rc, L.tab, ek);
+      S += exp_rel(max_raw(xr[i].y, lo), rc, L.tab, ek);
+      S += exp_rel(max_raw(xr[i].z, lo), rc, L.tab, ek);
+      S += exp_rel(max_raw(xr[i].w, lo), rc, L.tab, ek);
+      // keep the four exponentials of a load together: hoisting the first halves of all 32 costs a hundred registers
+      asm volatile("" : "+v"(S)::"memory");
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
+  if (w % c.R == 1) GR_TL(c, 23);
+  S = block_sum(S, L);                      // (its barrier also ends every read of the queue)
+  if (w % c.R == 1) GR_TL(c, 24);
+  const float lse = (float)((double)m + log(S));
+  const float bias = __fsub_rn(rm.s_in, lse);
+  if (w % c.R == 1) GR_TL(c, 26);
+  if (tid == 0) { st_agent(&c.row_bias[row], bias); st_agent(&c.row_mode[row], (int32_t)ROW_DENSE); }
+
+  // ---- candidates of the row that can still be among the W best
+  const uint32_t flat0 = (uint32_t)w * (uint32_t)V;
+  float t = *tau;
+  if (shared_tau) t = fmaxf(t, gr_ordkey_inv(shared_tau));     // what other workgroups of the request already know
+  *tau = t;
+  // The scan proper: a thread whose best candidate is below the threshold is done after one compare.  The
+  // others note their first two hits without branching (cheap, and no code per element beyond a few selects);
+  // the rare thread with more walks its 32 logits again from memory in a compact loop.
+  auto scan = [&](float tt) {
+    const float xt = fmaxf(logit_threshold(tt, bias), -3.0e38f);      // (finite: a masked entry, -inf, never passes)
+    if (lmax >= xt) {
+      float h0 = 0.f, h1 = 0.f;
+      int k0 = 0, k1 = 0, cnt = 0;
+#pragma unroll
+      for (int i = 0; i < kRegV4; i++) {
+#pragma unroll
+        for (int j = 0; j < 4; j++) {
+          const float xv = j == 0 ? xr[i].x : j == 1 ? xr[i].y : j == 2 ? xr[i].z : xr[i].w;
+          const bool hit = xv >= xt;
+          if (hit && cnt == 1) { h1 = xv; k1 = 4 * i + j; }
+          if (hit && cnt == 0) { h0 = xv; k0 = 4 * i + j; }
+          cnt += hit;
+        }
+      }
+      // element 4 i + j of this thread is token 4 (tid + i kT) + j
+      auto token_of = [&](int e) { return 4 * (tid + (e >> 2) * kT) + (e & 3); };
+      if (cnt <= 2) {
+        if (cnt >= 1) { const float sc = __fadd_rn(bias, h0); if (sc >= tt) pool_push(c, L, composite(sc, flat0 + (uint32_t)token_of(k0))); }
+        if (cnt >= 2) { const float sc = __fadd_rn(bias, h1); if (sc >= tt) pool_push(c, L, composite(sc, flat0 + (uint32_t)token_of(k1))); }
+      } else {
+        const float* xrow = c.logits + (size_t)row * V;
+        for (int i = 0; i < kRegV4; i++) {
+          const int pp = tid + i * kT;
+          if (pp >= nv4) break;
+          const float4 v4 = *(const float4*)(xrow + 4 * (size_t)pp);
+          const uint32_t nib = vbits >> (4 * i);
+          const float e4[4] = {v4.x, v4.y, v4.z, v4.w};
+#pragma unroll
+          for (int j = 0; j < 4; j++)
+            if (((nib >> j) & 1u) && e4[j] >= xt) {
+              const float sc = __fadd_rn(bias, e4[j]);
+              if (sc >= tt) pool_push(c, L, composite(sc, flat0 + (uint32_t)(4 * pp + j)));
+            }
+        }
+      }
+    }
+  };
+  // Nothing useful is known (or the threshold at hand let far too much through): bound the row by its own W-th
+  // best.  Every thread offers its two best valid candidates (2 kT >= 2 W of them); the bin in which the W-th best
+  // of those falls gives a score that at least W candidates of this row reach.
+  auto row_bound = [&](float t_now) -> float {
+    float a1 = -INFINITY, a2 = -INFINITY;
+#pragma unroll
+    for (int i = 0; i < kRegV4; i++) {
+      a2 = max_raw(a2, fminf(a1, xr[i].x)); a1 = max_raw(a1, xr[i].x);
+      a2 = max_raw(a2, fminf(a1, xr[i].y)); a1 = max_raw(a1, xr[i].y);
+      a2 = max_raw(a2, fminf(a1, xr[i].z)); a1 = max_raw(a1, xr[i].z);
+      a2 = max_raw(a2, fminf(a1, xr[i].w)); a1 = max_raw(a1, xr[i].w);
+    }
+    const float s1 = __fadd_rn(bias, a1), s2 = __fadd_rn(bias, a2);
+    const float worst = block_min((a2 > -INFINITY) ? s2 : ((a1 > -INFINITY) ? s1 : INFINITY), L);
+    const BinMap bm = bin_map(__fadd_rn(bias, m), worst);
+    for (int i = tid; i < kHistBins; i += kT) L.hist[i] = 0;
+    __syncthreads();
+    if (a1 > -INFINITY) atomicAdd(&L.hist[key_bin(bm, s1)], 1u);
+    if (a2 > -INFINITY) atomicAdd(&L.hist[key_bin(bm, s2)], 1u);
+    __syncthreads();
+    if (tid < 64) hist_threshold(L.hist, (uint32_t)c.W, L.thr, L.flag);
+    __syncthreads();
+    const int thr = *L.thr;
+    const bool enough = *L.flag >= (uint32_t)c.W;
+    float low = INFINITY;
+    if (a1 > -INFINITY && key_bin(bm, s1) <= thr) low = s1;
+    if (a2 > -INFINITY && key_bin(bm, s2) <= thr) low = s2;     // (s2 <= s1)
+    low = block_min(low, L);
+    return enough ? fmaxf(t_now, low) : t_now;   // fewer than W offers: the row keeps everything tau allows
+  };
+  bool boot = !(t > -INFINITY);
+  if (!boot) {
+    scan(t);
+    if (w % c.R == 1) GR_TL(c, 27);
+    __syncthreads();
+    if (*L.pn > (uint32_t)c.cap) {
+      // a threshold far below this row (another workgroup's, or one from much weaker rows) let too much through:
+      // take the row's pushes back and bound the row by its own W-th best instead
+      __syncthreads();
+      if (tid == 0) *L.pn = pn0;
+      if ((int)pn0 + c.W + kFlushSlack > c.cap) { if (!pool_thin(c, L, tau)) { *overflow = true; return; } }
+      t = *tau;
+      boot = true;
+    }
+  }
+  if (boot) {
+    scan(row_bound(t));
+    __syncthreads();
+    if (*L.pn > (uint32_t)c.cap) { *overflow = true; return; }
+  }
+  const uint32_t pn = *L.pn;
+  if (w % c.R == 1) GR_TL(c, 25);
   if ((int)pn >= c.cap / 2 || (!(*tau > -INFINITY) && (int)pn >= c.W)) {
     if (!pool_thin(c, L, tau)) { *overflow = true; return; }
     // let the other workgroups of the request profit at once
@@ -777,36 +1042,48 @@ __device__ __forceinline__ void finalize_request(const SelCtx& c, const MaskView
   // ---- order the survivors (descending composite key = score descending, flat index ascending)
   uint64_t* s_list = L.pool;
   const uint64_t* s_sorted = s_list;
-  if (n > 0 && 2 * n <= c.cap && n <= 4 * kT) {
-    // few survivors (the usual case, about W of them): rank every key by counting the larger ones.  Keys are distinct.
-    uint64_t* s_out = s_list + c.cap / 2;
-    if (n <= kT) {
-      const int parts = kT / n;                              // threads per key, each scanning its share of the list
-      const int i = tid / parts, part = tid % parts;
-      const int len = (n + parts - 1) / parts;
-      uint32_t* s_rank = L.hist;
-      for (int k = tid; k < n; k += kT) s_rank[k] = 0;
-      __syncthreads();
-      if (i < n) {
-        const uint64_t mine = s_list[i];
-        const int j1 = min(n, (part + 1) * len);
-        uint32_t cnt = 0;
-        for (int j = part * len; j < j1; j++) cnt += s_list[j] > mine;
-        if (cnt) atomicAdd(&s_rank[i], cnt);
-      }
-      __syncthreads();
-      if (tid < n) s_out[s_rank[tid]] = s_list[tid];
-    } else {
-      for (int i = tid; i < n; i += kT) {
-        const uint64_t mine = s_list[i];
-        uint32_t cnt = 0;
-        for (int j = 0; j < n; j++) cnt += s_list[j] > mine;
-        s_out[cnt] = mine;
-      }
-    }
-    s_sorted = s_out;
+  if (n > 1 && 2 * n <= c.cap) {
+    // Bucket order: the histogram bins are already ordered by score, so a survivor's place is the number of
+    // survivors in better bins plus its rank inside its own (tiny) bin.  Counting sort by bin into the upper half
+    // of the pool, then every survivor counts the larger keys of its bin.  Exact ties land in one bin and are
+    // ranked by the key's flat-index half there.
+    float top = -INFINITY, bottom = INFINITY;
+    for (int i = tid; i < n; i += kT) { const float sc = key_score(s_list[i]); top = fmaxf(top, sc); bottom = fminf(bottom, sc); }
+    top = block_max(top, L);
+    bottom = block_min(bottom, L);
+    const BinMap bm = bin_map(top, bottom);
+    for (int i = tid; i < kHistBins; i += kT) L.hist[i] = 0;
     __syncthreads();
-  } else if (n > 0) {
+    for (int i = tid; i < n; i += kT) atomicAdd(&L.hist[key_bin(bm, key_score(s_list[i]))], 1u);
+    __syncthreads();
+    {
+      // exclusive prefix over the bins, in place (each thread owns kHistBins / kT consecutive bins)
+      constexpr int per = kHistBins / kT;
+      uint32_t h[per], sum = 0;
+#pragma unroll
+      for (int k = 0; k < per; k++) { h[k] = L.hist[tid * per + k]; sum += h[k]; }
+      uint32_t total;
+      uint32_t run = block_excl_scan(sum, &total, L);
+#pragma unroll
+      for (int k = 0; k < per; k++) { L.hist[tid * per + k] = run; run += h[k]; }
+    }
+    __syncthreads();
+    uint64_t* s_tmp = s_list + c.cap / 2;
+    for (int i = tid; i < n; i += kT) {
+      const uint64_t key = s_list[i];
+      s_tmp[atomicAdd(&L.hist[key_bin(bm, key_score(key))], 1u)] = key;      // the bin's counter now runs to the bin's end
+    }
+    __syncthreads();
+    for (int q = tid; q < n; q += kT) {
+      const uint64_t key = s_tmp[q];
+      const int bin = key_bin(bm, key_score(key));
+      const int s0 = bin ? (int)L.hist[bin - 1] : 0, s1 = (int)L.hist[bin];
+      int cnt = 0;
+      for (int j = s0; j < s1; j++) cnt += s_tmp[j] > key;
+      s_list[s0 + cnt] = key;
+    }
+    __syncthreads();
+  } else if (n > 1) {
     int n2 = 1;
     while (n2 < n) n2 <<= 1;                                 // n <= cap, and cap is a power of two
     for (int i = n + tid; i < n2; i += kT) s_list[i] = 0;    // 0 sorts after every real key
@@ -872,60 +1149,109 @@ __device__ __forceinline__ void finalize_request(const SelCtx& c, const MaskView
   if (tid < kCtlWords) ctl[tid] = 0;
 }
 
-template <bool REG>
-__global__ void __launch_bounds__(kT) __attribute__((amdgpu_waves_per_eu(4, 8))) k_item(SelCtx c) {
+template <bool REG, int MODE>
+__global__ void __launch_bounds__(kT) __attribute__((amdgpu_waves_per_eu(3, 8))) k_item(SelCtx c) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
-  __shared__ float s_redf[kNW];
-  __shared__ double s_redd[kNW];
-  __shared__ uint32_t s_redu[kNW];
+  __shared__ float s_redf[2 * kNW];
+  __shared__ double s_redd[2 * kNW];
+  __shared__ uint32_t s_redu[2 * kNW];
   __shared__ uint32_t s_pn, s_flag;
   __shared__ int s_thr;
   Lds L;
   L.pool = (uint64_t*)smem;
   L.tab = (double*)(smem + (size_t)c.cap * 8);
-  L.hist = (uint32_t*)(L.tab + 64);
+  L.hist = (uint32_t*)(L.tab + kExpTab);
   L.mask = L.hist + kHistBins;
-  L.redf = s_redf; L.redd = s_redd; L.redu = s_redu; L.pn = &s_pn; L.thr = &s_thr; L.flag = &s_flag;
+  L.next = (float*)(L.mask + ((c.words + 3) & ~3));
+  L.redf = s_redf; L.redd = s_redd; L.redu = s_redu; L.par = 0; L.pn = &s_pn; L.thr = &s_thr; L.flag = &s_flag;
   const int tid = threadIdx.x, wave = tid >> 6;
   const int b = (int)blockIdx.x / c.G, g = (int)blockIdx.x % c.G;
-  if (tid < 64) L.tab[tid] = c_exp_tab[tid];
+  exp_table_init(L.tab);
   if (tid == 0) { s_pn = 0; s_flag = 0; }
   const ExpK ek = exp_consts();
   MaskView mv;
   mv.ok = true;
-  if (c.blob) mv = mask_view(c);
+  if (is_masked<MODE>(c)) mv = mask_view(c);
   __syncthreads();
 
   GR_TL(c, 0);
-  const int w0 = g * kRowsPerWG, w1 = min(c.W, w0 + kRowsPerWG);
+  const int w0 = g * c.R, w1 = min(c.W, w0 + c.R);
   float tau = -INFINITY;
   bool overflow = false;
-  // ---- streamed rows first (the whole workgroup on one row), gathered rows remembered.  A workgroup whose
-  // pool has overflowed still walks all its rows: the exact fallback needs every row's bias.
-  uint32_t sparse_rows = 0;
-  for (int w = w0; w < w1; w++) {
-    const int row = b * c.W + w;
-    const float s_in = c.scores_in[row];
-    if (!(s_in > -INFINITY)) {
-      if (tid == 0) { st_agent(&c.row_mode[row], (int32_t)ROW_DEAD); st_agent(&c.row_bias[row], -INFINITY); }
-      continue;
+  // ---- the workgroup's rows classified by one thread each (their chains of dependent loads run side by side)
+  __shared__ RowMeta s_meta[kMaxRows];
+  __shared__ uint32_t s_tauw;
+  if (tid < w1 - w0) {
+    const int row = b * c.W + w0 + tid;
+    RowMeta rm;
+    rm.s_in = c.scores_in[row];
+    rm.cls = ROW_DENSE; rm.n_list = -1; rm.t1 = -1; rm.list = nullptr;
+    if (!(rm.s_in > -INFINITY)) {
+      rm.cls = ROW_DEAD;
+      st_agent(&c.row_mode[row], (int32_t)ROW_DEAD); st_agent(&c.row_bias[row], -INFINITY);
+    } else if (is_masked<MODE>(c) && level_of<MODE>(c) >= 1) {
+      rm.n_list = 0;
+      if (mv.ok) row_children(c, mv, row, &rm.list, &rm.n_list);
+      if (level_of<MODE>(c) == 1) rm.t1 = c.prefix_in[(size_t)row * c.depth];
+      if (row_is_sparse(c, rm.n_list)) rm.cls = ROW_SPARSE;
     }
-    const int32_t* list = nullptr;
-    int n_list = 0;
-    if (c.blob && c.step >= 1) {
-      if (mv.ok) row_children(c, mv, row, &list, &n_list);
-      if (row_is_sparse(c, n_list)) { sparse_rows |= 1u << (w - w0); continue; }
+    s_meta[tid] = rm;
+  }
+  __syncthreads();
+  uint32_t dense_rows = 0, sparse_rows = 0;
+  for (int k = 0; k < w1 - w0; k++) {
+    if (s_meta[k].cls == ROW_DENSE) dense_rows |= 1u << k;
+    if (s_meta[k].cls == ROW_SPARSE) sparse_rows |= 1u << k;
+  }
+  // ---- streamed rows first (the whole workgroup on one row).  A workgroup whose pool has overflowed still
+  // walks all its rows: the exact fallback needs every row's bias.
+  if constexpr (REG) {
+    RowRegs cur;
+    uint32_t nmw[kRegV4];
+#pragma unroll
+    for (int i = 0; i < kRegV4; i++) nmw[i] = 0;
+    int k = dense_rows ? __ffs(dense_rows) - 1 : -1;
+    uint32_t tw = 0;
+    if (k >= 0) row_prefetch<MODE>(c, mv, L, b * c.W + w0 + k, s_meta[k], nmw);
+    while (k >= 0) {
+      dense_rows &= dense_rows - 1;
+      const int kn = dense_rows ? __ffs(dense_rows) - 1 : -1;
+      row_take(c, L, cur);
+      if (k == 1) GR_TL(c, 28);
+      if (tid == 0) s_tauw = tw;            // (requested a row ago: any older value of the threshold is just as valid)
+      // the request's shared threshold: one relaxed read for the whole workgroup, used by the NEXT row so that
+      // nobody waits for it
+      if (tid == 0) tw = ld_agent(&c.ctl[(size_t)b * kCtlWords + CTL_TAU]);
+#pragma unroll
+      for (int i = 0; i < kRegV4; i++) cur.mw[i] = nmw[i];
+      if (kn >= 0) row_prefetch<MODE>(c, mv, L, b * c.W + w0 + kn, s_meta[kn], nmw);
+      if (k == 1) GR_TL(c, 29);
+      __syncthreads();
+      if (k == 1) GR_TL(c, 30);
+      const uint32_t shared_tau = s_tauw;
+      row_process<MODE>(c, mv, L, ek, b * c.W + w0 + k, w0 + k, s_meta[k], cur, shared_tau, &tau, &overflow);
+      if (k < 8) GR_TL(c, 1 + k);
+      __syncthreads();                      // (s_tauw is rewritten for the next row)
+      k = kn;
     }
-    dense_row<REG>(c, mv, L, ek, row, w, s_in, list, n_list, &tau, &overflow);
-    GR_TL(c, 1 + (w - w0));
+  } else {
+    while (dense_rows) {
+      const int k = __ffs(dense_rows) - 1;
+      dense_rows &= dense_rows - 1;
+      const RowMeta rm = s_meta[k];
+      dense_row<false>(c, mv, L, ek, b * c.W + w0 + k, w0 + k, rm.s_in, rm.list, max(rm.n_list, 0), &tau, &overflow);
+      if (k < 8) GR_TL(c, 1 + k);
+    }
   }
   GR_TL(c, 9);
   // ---- gathered rows, one per wavefront, kNW at a time
   while (sparse_rows) {
-    // the wave-th set bit of the next kNW
+    // the wave-th set bit of the next kNW (fewer while no threshold exists: such a row pushes all its children)
     uint32_t bits = sparse_rows;
     int mine = -1;
-    for (int k = 0; k < kNW && bits; k++) {
+    const int room = (c.cap - (int)min(s_pn, (uint32_t)c.cap)) / kSparseMax;
+    const int per_round = (tau > -INFINITY) ? kNW : max(1, min(kNW, room));
+    for (int k = 0; k < per_round && bits; k++) {
       const int i = __ffs(bits) - 1;
       bits &= bits - 1;
       if (k == wave) mine = i;
@@ -933,10 +1259,7 @@ __global__ void __launch_bounds__(kT) __attribute__((amdgpu_waves_per_eu(4, 8)))
     sparse_rows = bits;
     if (mine >= 0) {
       const int w = w0 + mine, row = b * c.W + w;
-      const int32_t* list = nullptr;
-      int n = 0;
-      if (mv.ok) row_children(c, mv, row, &list, &n);
-      sparse_row(c, L, ek, row, w, c.scores_in[row], list, n, tau);
+      sparse_row(c, L, ek, row, w, s_meta[mine].s_in, s_meta[mine].list, s_meta[mine].n_list, tau);
     }
     __syncthreads();
     const uint32_t pn = s_pn;
@@ -1001,7 +1324,18 @@ __global__ void __launch_bounds__(kT) __attribute__((amdgpu_waves_per_eu(4, 8)))
   if (!s_flag) return;
   if (tid == 0) s_pn = 0;
   __syncthreads();
-  finalize_request(c, mv, L, b);
+  {
+    // The parameters are read again from the kernel-argument segment (this kernel's only argument sits at its
+    // start) through a pointer the compiler cannot see through: the dozen output pointers that only this last step
+    // needs would otherwise sit in scalar registers during the whole row loop.
+    const SelCtx* cp = (const SelCtx*)__builtin_amdgcn_kernarg_segment_ptr();
+    asm volatile("" : "+s"(cp));
+    const SelCtx cf = *cp;
+    MaskView mvf;
+    mvf.ok = true;
+    if (cf.blob) mvf = mask_view(cf);
+    finalize_request(cf, mvf, L, b);
+  }
   GR_TL(c, 20);
 }
 
@@ -1013,16 +1347,25 @@ __global__ void __launch_bounds__(256) k_item_init(uint32_t* ctl, int n) {
 // Room for a thinned pool (about W) plus everything one row may add after being bounded by its own W-th best
 // (about W again) plus slack.
 int pool_cap(int W) {
-  int cap = 2048;
+  int cap = 1024;
   while (cap < 2 * W + 2 * kFlushSlack) cap <<= 1;
   return cap;
 }
 
-struct SelLayout { size_t off_bias, off_mode, off_ctl, off_list, total; int G, cap, flush_cap; };
+// Rows per workgroup: 8, unless a few more (up to kMaxRows) let ALL workgroups of the launch be resident at once
+// (3 per CU x 256 CUs): a launch that needs a second round of workgroups pays a whole workgroup lifetime for it.
+int rows_per_wg(int B, int W) {
+  constexpr int kResident = 3 * 256;
+  for (int r = 8; r <= kMaxRows; r++)
+    if ((int64_t)B * ((W + r - 1) / r) <= kResident) return r;
+  return 8;
+}
+struct SelLayout { size_t off_bias, off_mode, off_ctl, off_list, total; int R, G, cap, flush_cap; };
 SelLayout sel_layout(int B, int W) {
   SelLayout l;
   const size_t rows = (size_t)B * W;
-  l.G = (W + kRowsPerWG - 1) / kRowsPerWG;
+  l.R = rows_per_wg(B, W);
+  l.G = (W + l.R - 1) / l.R;
   l.cap = pool_cap(W);
   l.flush_cap = W + kFlushSlack;
   size_t o = 0;
@@ -1067,7 +1410,7 @@ gr_status gr_select_launch(const gr_select_params* p, void* workspace, size_t wo
 #endif
   c.B = p->B; c.W = p->W; c.V = p->V; c.depth = p->depth; c.step = p->step; c.flags = p->flags;
   c.vec4 = (p->V % 4 == 0) && (((uintptr_t)p->logits & 15) == 0);
-  c.G = lay.G; c.cap = lay.cap; c.flush_cap = lay.flush_cap;
+  c.R = lay.R; c.G = lay.G; c.cap = lay.cap; c.flush_cap = lay.flush_cap;
   c.words = (p->V + 31) / 32;
   c.blob = (const char*)p->mask;
   c.logits = p->logits; c.scores_in = p->scores_in; c.prefix_in = p->prefix_in; c.range_in = p->range_in;
@@ -1083,16 +1426,25 @@ gr_status gr_select_launch(const gr_select_params* p, void* workspace, size_t wo
     const int n = p->B * kCtlWords;
     hipLaunchKernelGGL(k_item_init, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, c.ctl, n);
   }
-  const size_t lds = (size_t)c.cap * 8 + 64 * 8 + (size_t)kHistBins * 4 + (size_t)c.words * 4;
-  const bool reg = c.vec4 && p->V <= kRegV4 * 4 * kT;
+  const bool reg = c.vec4 && p->V <= kRegV4 * 4 * kT && p->W <= kT;
+  const size_t lds = (size_t)c.cap * 8 + (size_t)kExpTab * 8 + (size_t)kHistBins * 4 + (size_t)((c.words + 3) & ~3) * 4 +
+                     (reg ? (size_t)kRegV4 * kT * 16 : 0);
   const unsigned grid = (unsigned)((int64_t)p->B * lay.G);
-  if (reg) {
-    if (lds > 64 * 1024) GR_HIP_TRY(hipFuncSetAttribute((const void*)k_item<true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    hipLaunchKernelGGL(k_item<true>, dim3(grid), dim3(kT), lds, stream, c);
-  } else {
-    if (lds > 64 * 1024) GR_HIP_TRY(hipFuncSetAttribute((const void*)k_item<false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    hipLaunchKernelGGL(k_item<false>, dim3(grid), dim3(kT), lds, stream, c);
+  const int mode = !reg ? -1 : (!p->mask ? 0 : 1 + p->step);
+#define GR_LAUNCH_ITEM(REG_, MODE_)                                                                                          \
+  do {                                                                                                                      \
+    if (lds > 64 * 1024)                                                                                                    \
+      GR_HIP_TRY(hipFuncSetAttribute((const void*)k_item<REG_, MODE_>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)); \
+    hipLaunchKernelGGL((k_item<REG_, MODE_>), dim3(grid), dim3(kT), lds, stream, c);                                        \
+  } while (0)
+  switch (mode) {
+    case 0: GR_LAUNCH_ITEM(true, 0); break;
+    case 1: GR_LAUNCH_ITEM(true, 1); break;
+    case 2: GR_LAUNCH_ITEM(true, 2); break;
+    case 3: GR_LAUNCH_ITEM(true, 3); break;
+    default: GR_LAUNCH_ITEM(false, -1); break;
   }
+#undef GR_LAUNCH_ITEM
   GR_HIP_TRY(hipGetLastError());
   return GR_OK;
 }
