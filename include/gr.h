@@ -134,11 +134,7 @@ gr_status gr_item_mask_build(const int32_t* items_sorted, int64_t n_items, int32
  * Supported: depth == 3; 1 <= W <= 2048; 1 <= V <= 32768; W*V < 2^31.
  * ------------------------------------------------------------------------------------------------ */
 enum {
-  GR_SELECT_FORCE_DENSE = 1,    /* stream every live row in full even when a sparse gather would be cheaper */
-  GR_SELECT_WORKSPACE_CLEAN = 2 /* the caller states that the last use of `workspace` was a gr_beam_select call   */
-                                /* (any shape with the same B) that has completed or precedes this one on the     */
-                                /* same stream: the call then skips the small kernel that clears the per-request  */
-                                /* control words (Section 6.3: structures set up once and reused)                 */
+  GR_SELECT_FORCE_DENSE = 1     /* stream every live row in full even when a sparse gather would be cheaper */
 };
 
 typedef struct {

@@ -48,10 +48,6 @@ static inline void gr_mask_layout(int64_t n_items, int32_t V, gr_mask_header* h)
   h->total_bytes = (int64_t)o;
 }
 
-// gr_beam_select behind the argument marshalling (shared by the entry points that differ only in where the
-// workspace comes from)
-gr_status gr_select_launch(const gr_select_params* p, void* workspace, size_t workspace_bytes, hipStream_t stream);
-
 #ifdef __HIPCC__
 // ------------------------------------------------------------------ wave64 primitives
 __device__ __forceinline__ int gr_lane() { return (int)__lane_id(); }
