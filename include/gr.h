@@ -64,7 +64,7 @@ typedef struct {
                               /* number of valid decode tokens this step                            */
   int32_t max_L;              /* host copy of max_b L_b (sizes the launch; no device read-back)     */
   int64_t total_L;            /* host copy of sum_b L_b = cu_seqlens[B]                             */
-  float   sm_scale;           /* softmax scale, normally 1/sqrt(d)                                  */
+  float   sm_scale;           /* softmax scale, normally 1/sqrt(d); must be positive and finite     */
   const void*    q;           /* bf16 [B, W, Hq, d]                                                 */
   const void*    k_shared;    /* bf16 [total_L, Hkv, d]; request b = rows cu_seqlens[b]..[b+1]      */
   const void*    v_shared;    /* bf16 [total_L, Hkv, d]                                             */
@@ -159,6 +159,22 @@ size_t gr_beam_select_workspace_bytes(int32_t B, int32_t W, int32_t V, int32_t d
 /* Enqueue the item step.  `workspace`: device, 256-byte aligned, contents unspecified before and
  * after.  Errors: INVALID_ARG, UNSUPPORTED, WORKSPACE_TOO_SMALL, HIP. */
 gr_status gr_beam_select(const gr_select_params* p, void* workspace, size_t workspace_bytes, void* stream);
+
+/* ------------------------------------------------------------------------------------------------
+ * gr_beam_select_noalloc - gr_beam_select for callers that cannot allocate device memory or carry a
+ * workspace around: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ *
+ * Same parameters, same results and same errors as gr_beam_select; the workspace is a static device array
+ * inside the library (gr_beam_select_noalloc_max_workspace_bytes() bytes, 16 MiB: on every GPU the library
+ * runs on until the process ends).  A shape whose gr_beam_select_workspace_bytes() exceeds that limit is
+ * rejected with GR_ERR_WORKSPACE_TOO_SMALL before anything is enqueued (at V = 8192 the limit is about 16 000
+ * beam rows, B * W).  The call allocates nothing and frees nothing; the first call on a device looks up the
+ * array's address on that device (no synchronisation).  All calls on one GPU share the array: calls that
+ * overlap in time on one GPU (different streams, different host threads) race and give undefined results -
+ * order them, or use gr_beam_select with separate workspaces.
+ * ------------------------------------------------------------------------------------------------ */
+size_t    gr_beam_select_noalloc_max_workspace_bytes(void);
+gr_status gr_beam_select_noalloc(const gr_select_params* p, void* stream);
 
 /* ------------------------------------------------------------------------------------------------
  * gr_beam_reorder - in-place update of the unshared cache between two decode steps (Section 5.1).

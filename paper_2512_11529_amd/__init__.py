@@ -16,7 +16,8 @@ import os
 
 from . import build as _build
 
-__all__ = ["load_library", "gr_beam_attn", "gr_item_mask_build", "gr_beam_select", "gr_beam_reorder", "gr_status_string",
+__all__ = ["load_library", "gr_beam_attn", "gr_item_mask_build", "gr_beam_select", "gr_beam_select_noalloc", "gr_beam_reorder",
+           "gr_status_string",
            "attn_workspace_bytes", "select_workspace_bytes", "GrError", "GR_SELECT_FORCE_DENSE", "LIB_PATH"]
 
 LIB_PATH = _build.LIB_PATH
@@ -74,6 +75,10 @@ def load_library(path: str = None):
     lib.gr_beam_select_workspace_bytes.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32]
     lib.gr_beam_select.restype = ctypes.c_int32
     lib.gr_beam_select.argtypes = [ctypes.POINTER(_SelectParams), ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+    lib.gr_beam_select_noalloc.restype = ctypes.c_int32
+    lib.gr_beam_select_noalloc.argtypes = [ctypes.POINTER(_SelectParams), ctypes.c_void_p]
+    lib.gr_beam_select_noalloc_max_workspace_bytes.restype = ctypes.c_size_t
+    lib.gr_beam_select_noalloc_max_workspace_bytes.argtypes = []
     lib.gr_beam_reorder.restype = ctypes.c_int32
     lib.gr_beam_reorder.argtypes = [ctypes.c_int32] * 6 + [ctypes.c_void_p] * 4
     _lib = lib
@@ -150,7 +155,7 @@ def gr_beam_attn(q, k_shared, v_shared, cu_seqlens, k_unshared, v_unshared, u, s
     p = _attn_params(q, k_shared, v_shared, cu_seqlens, k_unshared, v_unshared, u, sm_scale, max_L, total_L, out, lse_out)
     need = int(lib.gr_beam_attn_workspace_bytes(ctypes.byref(p)))
     if workspace is None and need > 0:
-        workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+        workspace = _scratch(need, q.device, stream)
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     rc = lib.gr_beam_attn(ctypes.byref(p), _ptr(workspace), ws_bytes, _stream(stream))
     if rc != 0:
@@ -179,12 +184,18 @@ def select_workspace_bytes(B, W, V, depth) -> int:
     return int(load_library().gr_beam_select_workspace_bytes(B, W, V, depth))
 
 
-def gr_beam_select(mask, logits, scores_in, prefix_in, range_in, step, flags=0, out=None, workspace=None, stream=None):
-    """Beam item step.  logits fp32 [B,W,V]; scores_in fp32 [B,W]; prefix_in int32 [B,W,depth]; range_in int32
-    [B,W,2]; mask = blob from gr_item_mask_build or None.  `out` may hold preallocated tensors under the keys
-    parent, token, scores, prefix, range, item_index.  Returns that dict.  Enqueues on `stream`."""
+def _scratch(nbytes, device, stream):
+    """A workspace the wrapper allocates itself belongs to the stream the kernels run on: allocated under another
+    stream, the caching allocator could hand the block out again while they still use it."""
     import torch
-    lib = load_library()
+    if stream is None:
+        return torch.empty(nbytes, dtype=torch.uint8, device=device)
+    with torch.cuda.stream(stream):
+        return torch.empty(nbytes, dtype=torch.uint8, device=device)
+
+
+def _select_call(mask, logits, scores_in, prefix_in, range_in, step, flags, out, allocate_outputs):
+    import torch
     B, W, V = logits.shape
     depth = prefix_in.shape[2]
     _check(logits, torch.float32, None, "logits")
@@ -198,11 +209,10 @@ def gr_beam_select(mask, logits, scores_in, prefix_in, range_in, step, flags=0, 
                 prefix=((B, W, depth), torch.int32), range=((B, W, 2), torch.int32), item_index=((B, W), torch.int32))
     for k, (shape, dt) in spec.items():
         if k not in out or out[k] is None:
+            if not allocate_outputs:
+                raise ValueError(f"out[{k!r}] must be preallocated for a call that allocates nothing")
             out[k] = torch.empty(shape, dtype=dt, device=dev)
         _check(out[k], dt, shape, k)
-    need = int(lib.gr_beam_select_workspace_bytes(B, W, V, depth))
-    if workspace is None:
-        workspace = torch.empty(need, dtype=torch.uint8, device=dev)
     p = _SelectParams()
     p.B, p.W, p.V, p.depth, p.step, p.flags = B, W, V, depth, int(step), int(flags)
     p.mask = mask.data_ptr() if mask is not None else None
@@ -210,9 +220,31 @@ def gr_beam_select(mask, logits, scores_in, prefix_in, range_in, step, flags=0, 
     p.prefix_in, p.range_in = prefix_in.data_ptr(), range_in.data_ptr()
     p.parent_out, p.token_out, p.scores_out = out["parent"].data_ptr(), out["token"].data_ptr(), out["scores"].data_ptr()
     p.prefix_out, p.range_out, p.item_index_out = out["prefix"].data_ptr(), out["range"].data_ptr(), out["item_index"].data_ptr()
+    return p, out
+
+
+def gr_beam_select(mask, logits, scores_in, prefix_in, range_in, step, flags=0, out=None, workspace=None, stream=None):
+    """Beam item step.  logits fp32 [B,W,V]; scores_in fp32 [B,W]; prefix_in int32 [B,W,depth]; range_in int32
+    [B,W,2]; mask = blob from gr_item_mask_build or None.  `out` may hold preallocated tensors under the keys
+    parent, token, scores, prefix, range, item_index.  Returns that dict.  Enqueues on `stream`."""
+    lib = load_library()
+    p, out = _select_call(mask, logits, scores_in, prefix_in, range_in, step, flags, out, True)
+    if workspace is None:
+        workspace = _scratch(int(lib.gr_beam_select_workspace_bytes(p.B, p.W, p.V, p.depth)), logits.device, stream)
     rc = lib.gr_beam_select(ctypes.byref(p), _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream))
     if rc != 0:
         raise GrError(rc, "gr_beam_select")
+    return out
+
+
+def gr_beam_select_noalloc(mask, logits, scores_in, prefix_in, range_in, step, out, flags=0, stream=None):
+    """The same item step through the entry point that allocates nothing: the workspace is a static device array inside
+    the library and every output tensor must be passed in `out`.  Calls that overlap on one GPU race."""
+    lib = load_library()
+    p, out = _select_call(mask, logits, scores_in, prefix_in, range_in, step, flags, out, False)
+    rc = lib.gr_beam_select_noalloc(ctypes.byref(p), _stream(stream))
+    if rc != 0:
+        raise GrError(rc, "gr_beam_select_noalloc")
     return out
 
 

@@ -695,6 +695,7 @@ extern "C" gr_status gr_beam_attn(const gr_attn_params* p, void* workspace, size
   if (p->total_L > 0 && (!p->k_shared || !p->v_shared)) return GR_ERR_INVALID_ARG;
   if (p->u > 0 && (!p->k_unshared || !p->v_unshared)) return GR_ERR_INVALID_ARG;
   if (p->Hq % p->Hkv) return GR_ERR_INVALID_ARG;
+  if (!(p->sm_scale > 0.f) || !(p->sm_scale < INFINITY)) return GR_ERR_INVALID_ARG;   // (also rejects NaN: the lazy-maximum test assumes a positive scale)
   if (p->d != 64 && p->d != 128) return GR_ERR_UNSUPPORTED;
   if (p->total_L >= ((int64_t)1 << 31)) return GR_ERR_UNSUPPORTED;
   if ((int64_t)p->max_L * p->Hkv * p->d * 2 >= ((int64_t)1 << 32)) return GR_ERR_UNSUPPORTED;   // one request's K (or V) must fit a buffer descriptor

@@ -255,6 +255,22 @@ __device__ __forceinline__ void row_dense(const SelCtx& c, int owns_dead, int ro
     return;                                        // the keys of a dead row are never read
   }
   const int V = c.V;
+  const float* x = c.logits + (size_t)row * V;
+  const bool reg = c.vec4 && V <= kRegV4 * 4 * kRowThreads;
+  // ---- the row is requested as early as it is known to be streamed (one HBM read: it stays in registers): at
+  // once when no child count can turn it into a gathered row, else after the look-up of its children
+  const int nv4 = V >> 2;
+  float4 xr[kRegV4];
+  auto request_row = [&]() {
+#pragma unroll
+    for (int i = 0; i < kRegV4; i++) {
+      const int p = tid + i * kRowThreads;
+      xr[i] = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
+      if (p < nv4) xr[i] = *(const float4*)(x + 4 * (size_t)p);
+    }
+  };
+  const bool surely_streamed = !c.blob || c.step == 0 || (c.flags & GR_SELECT_FORCE_DENSE);
+  if (reg && surely_streamed) request_row();
   const int32_t* list = nullptr;
   int n_list = 0;
   MaskView mv;
@@ -266,19 +282,7 @@ __device__ __forceinline__ void row_dense(const SelCtx& c, int owns_dead, int ro
       if (row_is_sparse(c, n_list)) return;      // a gathered row: rows_sparse owns it
     }
   }
-  const float* x = c.logits + (size_t)row * V;
-  const bool reg = c.vec4 && V <= kRegV4 * 4 * kRowThreads;
-  // ---- the row is requested first (one HBM read: it stays in registers)
-  const int nv4 = V >> 2;
-  float4 xr[kRegV4];
-  if (reg) {
-#pragma unroll
-    for (int i = 0; i < kRegV4; i++) {
-      const int p = tid + i * kRowThreads;
-      xr[i] = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
-      if (p < nv4) xr[i] = *(const float4*)(x + 4 * (size_t)p);
-    }
-  }
+  if (reg && !surely_streamed) request_row();
   if (tid < 64) s_tab[tid] = c_exp_tab[tid];
   const ExpK ek = exp_consts();
   const int words = (V + 31) >> 5;
@@ -1012,3 +1016,36 @@ extern "C" gr_status gr_beam_select(const gr_select_params* p, void* workspace, 
   GR_HIP_TRY(hipGetLastError());
   return GR_OK;
 }
+
+// ------------------------------------------------------------------------------------------------
+// gr_beam_select_noalloc: the same item step for callers that cannot allocate or hand in a workspace.
+// The kernels' scratch memory (row bias / mode / best score and the chunk keys) lives in a static device
+// array; every GPU the library runs on holds its own copy at its own address, obtained once per device.
+// ------------------------------------------------------------------------------------------------
+namespace {
+constexpr size_t kStaticScratchBytes = (size_t)16 << 20;
+constexpr int kMaxDevices = 64;
+__device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+void* g_scratch_ptr[kMaxDevices];          // device address of `scratch` per device (0 = not looked up yet)
+}  // namespace
+
+extern "C" size_t gr_beam_select_noalloc_max_workspace_bytes(void) { return kStaticScratchBytes; }
+
+extern "C" gr_status gr_beam_select_noalloc(const gr_select_params* p, void* stream_) {
+  if (!p) return GR_ERR_INVALID_ARG;
+  if (p->B <= 0 || p->W <= 0 || p->V <= 0 || p->depth <= 0) return GR_ERR_INVALID_ARG;
+  if (gr_beam_select_workspace_bytes(p->B, p->W, p->V, p->depth) > kStaticScratchBytes) return GR_ERR_WORKSPACE_TOO_SMALL;
+  int dev = -1;
+  GR_HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return GR_ERR_UNSUPPORTED;
+  if (!g_scratch_ptr[dev]) {
+    // (the array's name is only a host-side handle: its device address on the current device is asked for once)
+    void* ptr = nullptr;
+    GR_HIP_TRY(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+    if (!ptr) return GR_ERR_HIP;
+    g_scratch_ptr[dev] = ptr;
+  }
+  // nothing in the workspace has to start at zero: every word a call reads is written by that call first
+  return gr_beam_select(p, g_scratch_ptr[dev], kStaticScratchBytes, stream_);
+}
+
