@@ -1,9 +1,12 @@
 """GPU parity at the full benchmark sizes (workloads 2-5), in the launch configuration bench.py times.
 
 Item step: every request, every level, bit-exact against the oracle's full sort (it is cheap enough
-on the CPU).  Attention: the GPU output of the whole batch is compared with the oracle on a seeded
-sample of (request, beam, head) rows, each of which the oracle computes from its own unified copy
-of that beam's KV sequence; plus properties that hold for every row (finite outputs, lse finite).
+on the CPU), with the mask, forced dense, and without a mask.  Attention: for every decode step
+(u = 1, 2, 3) the GPU output of the whole batch is compared with the oracle on a stratified sample of
+(request, beam, head) rows - every (request, KV head, 256-row block, 32-row wavefront slice) of the
+launch is visited, plus the first and last row of every block - each of which the oracle computes
+from its own unified copy of that beam's KV sequence; plus properties that hold for every row
+(finite outputs, lse finite).
 """
 import numpy as np
 import pytest
@@ -54,22 +57,44 @@ def test_item_step_all_levels_bit_exact(gr, oracle_lib, config_id):
     np.testing.assert_array_equal(items[g["item_index"]], g["prefix"])
 
 
-@pytest.mark.parametrize("config_id", [2])
-def test_item_step_unconstrained_full_size(gr, oracle_lib, config_id):
+@pytest.mark.parametrize("config_id,step", [(2, 0), (3, 1), (3, 2)])
+def test_item_step_unconstrained_full_size(gr, oracle_lib, config_id, step):
+    """mask = NULL with every beam live: the worst case for the item step (every logit is a candidate)."""
     cfg = gr_synth.get_config(config_id)
-    logits = gr_synth.make_logits(cfg, 1)
-    rng = np.random.default_rng(5)
+    logits = gr_synth.make_logits(cfg, step)
+    rng = np.random.default_rng(5 + step)
     sc = np.sort(-4.0 * rng.random((cfg.B, cfg.W)).astype(np.float32), axis=1)[:, ::-1].copy()
-    pf = np.full((cfg.B, cfg.W, cfg.ND), -1, np.int32)
+    pf = rng.integers(0, cfg.V, size=(cfg.B, cfg.W, cfg.ND)).astype(np.int32)
+    pf[:, :, step:] = -1
     rg = np.zeros((cfg.B, cfg.W, 2), np.int32)
-    got = gr.gr_beam_select(None, to_dev(logits), to_dev(sc), to_dev(pf), to_dev(rg), 0)
+    got = gr.gr_beam_select(None, to_dev(logits), to_dev(sc), to_dev(pf), to_dev(rg), step)
     torch.cuda.synchronize()
-    want = oracle_lib.beam_select(None, logits, sc, pf, 0)
-    assert_select_equal({k: v.cpu().numpy() for k, v in got.items()}, want)
+    want = oracle_lib.beam_select(None, logits, sc, pf, step)
+    g = {k: v.cpu().numpy() for k, v in got.items()}
+    assert_select_equal(g, want, f"config {config_id} step {step} no mask")
+    assert np.isfinite(g["scores"]).all() and (np.diff(g["scores"], axis=1) <= 0).all()
+
+
+def _stratified_rows(cfg, rng):
+    """(b, w, hq) triples that visit every (request, KV head, 256-row block, 32-row wavefront slice) of the attention
+    launch at least once, plus the first and the last query row of every block."""
+    g = cfg.Hq // cfg.Hkv
+    M = cfg.W * g                                    # query rows that share one KV head of one request
+    tri = []
+    for b in range(cfg.B):
+        for kvh in range(cfg.Hkv):
+            for r0 in range(0, M, 256):
+                r1 = min(M, r0 + 256)
+                rows = {r0, r1 - 1}
+                for s0 in range(r0, r1, 32):
+                    rows.add(int(rng.integers(s0, min(r1, s0 + 32))))
+                for r in rows:
+                    tri.append((b, r // g, kvh * g + r % g))
+    return np.array(tri, dtype=np.int32)
 
 
 @pytest.mark.parametrize("config_id", [2, 3, 4, 5])
-def test_attention_sampled_rows(gr, oracle_lib, config_id):
+def test_attention_stratified_rows(gr, oracle_lib, config_id):
     cfg = gr_synth.get_config(config_id)
     print(f"config {config_id}: generating K/V", flush=True)
     cu = gr_synth.make_prompt_lengths(cfg)
@@ -78,8 +103,7 @@ def test_attention_sampled_rows(gr, oracle_lib, config_id):
     lens = np.diff(cu)
     scale = float(np.float32(1.0 / np.sqrt(cfg.d)))
     rng = np.random.default_rng(config_id)
-    for step in (0, 2):
-        print(f"config {config_id}: attention u={step + 1}", flush=True)
+    for step in range(cfg.ND):                       # u = 1, 2, 3
         a = gr_synth.make_attention_inputs(cfg, step, kv_shared=kv)
         lse = torch.empty((cfg.B, cfg.W, cfg.Hq), dtype=torch.float32, device=dev())
         out, _ = gr.gr_beam_attn(bf16_to_dev(a["q"]), d_k, d_v, d_cu, bf16_to_dev(a["k_unshared"]), bf16_to_dev(a["v_unshared"]),
@@ -88,11 +112,8 @@ def test_attention_sampled_rows(gr, oracle_lib, config_id):
         out = out.float().cpu().numpy()
         lse = lse.cpu().numpy()
         assert np.isfinite(out).all() and np.isfinite(lse).all()
-        n = 96
-        tri = np.stack([rng.integers(0, cfg.B, n), rng.integers(0, cfg.W, n), rng.integers(0, cfg.Hq, n)], axis=1).astype(np.int32)
-        # always include the corners of the batch and the shortest / longest prompt
-        tri[0] = (0, 0, 0); tri[1] = (cfg.B - 1, cfg.W - 1, cfg.Hq - 1)
-        tri[2] = (int(lens.argmin()), cfg.W // 2, 1); tri[3] = (int(lens.argmax()), cfg.W - 1, cfg.Hq - 2)
+        tri = _stratified_rows(cfg, rng)
+        print(f"config {config_id}: attention u={step + 1}, {len(tri)} rows against the oracle", flush=True)
         ref, ref_lse = oracle_lib.attn_unified(a["q"], a["k_shared"], a["v_shared"], cu, a["k_unshared"], a["v_unshared"], a["u"], scale, tri)
         got = out[tri[:, 0], tri[:, 1], tri[:, 2]]
         err = np.abs(got - ref).max()

@@ -1,6 +1,7 @@
 """GPU: one decode step (attention -> item step -> cache reorder) captured as a HIP graph replays to
-the eager results.  The entry points only enqueue kernels on the caller's stream (no allocation, no
-synchronisation, no memset nodes), which is what makes the step capturable as a whole."""
+the oracle's results (attention within 2e-2, beams and the reordered cache bit-exact) and to the eager
+step's, on every replay.  The entry points only enqueue kernels on the caller's stream (no allocation,
+no synchronisation, no memset nodes), which is what makes the step capturable as a whole."""
 import numpy as np
 import pytest
 
@@ -10,7 +11,7 @@ from gpu_util import bf16_to_dev, to_dev
 pytestmark = pytest.mark.gpu
 
 
-def test_step_graph_replays_match_eager():
+def test_step_graph_replays_match_oracle_and_eager(oracle_lib):
     import torch
     import paper_2512_11529_amd as gr
     gr.load_library()
@@ -45,6 +46,26 @@ def test_step_graph_replays_match_eager():
     torch.cuda.synchronize()
     want = dict(out=out.clone(), ku=ku.clone(), vu=vu.clone(), **{k: v.clone() for k, v in sel.items()})
 
+    # what the oracle says the step must produce
+    ref_out, _ = oracle_lib.attn_unified(a["q"], a["k_shared"], a["v_shared"], cu, a["k_unshared"], a["v_unshared"], 2, scale)
+    ref_out = ref_out.reshape(B, W, Hq, d)
+    st0_host = {k: v.cpu().numpy() for k, v in st0.items()}
+    ref_sel = oracle_lib.beam_select(items, gr_synth.make_logits(cfg, 1), st0_host["scores"], st0_host["prefix"], 1)
+    ref_ku = oracle_lib.unshared_reorder(a["k_unshared"].copy(), ref_sel["parent"])
+    ref_vu = oracle_lib.unshared_reorder(a["v_unshared"].copy(), ref_sel["parent"])
+
+    def check_against_oracle(got, what):
+        err = np.abs(got["out"].float().cpu().numpy() - ref_out).max()
+        assert err <= 2e-2, f"{what}: attention max-abs {err}"
+        for k in ("parent", "token", "prefix", "range", "item_index"):
+            np.testing.assert_array_equal(got[k].cpu().numpy(), ref_sel[k], err_msg=f"{what}: {k}")
+        np.testing.assert_allclose(got["scores"].cpu().numpy(), ref_sel["scores"], rtol=1e-5, atol=0, err_msg=f"{what}: scores")
+        for name, ref in (("ku", ref_ku), ("vu", ref_vu)):
+            bits = got[name].view(torch.int16).cpu().numpy().view(np.uint16)
+            np.testing.assert_array_equal(bits[:, :, :2], ref[:, :, :2], err_msg=f"{what}: reordered {name}")
+
+    check_against_oracle(want, "eager step")
+
     def reset():
         ku.copy_(ku0); vu.copy_(vu0); out.zero_()
         for v in sel.values():
@@ -67,5 +88,6 @@ def test_step_graph_replays_match_eager():
         g.replay()
         torch.cuda.synchronize()
         got = dict(out=out, ku=ku, vu=vu, **sel)
+        check_against_oracle(got, f"replay {rep}")
         for k in want:
             assert torch.equal(got[k], want[k]), f"replay {rep}: {k} differs from the eager step"
