@@ -4,9 +4,13 @@
 A step = one decode step over the whole batch: gr_beam_attn (u = s+1 own tokens per beam) followed
 by gr_beam_select at trie level s, for s cycling 0,1,2.  Inputs are synthetic (gr_synth), resident
 in HBM before the timed region; the beam state fed to level s is the real state produced by levels
-0..s-1.  Prints ONE JSON line.
+0..s-1.  Prints ONE JSON line: the headline (steps/s), `roofline` (attention, bf16 MFMA), `roofline_select`
+(item step on its dense paths, HBM), `cpu_baseline` (the oracle on the host cores), and extras measured
+outside the headline's timed region (cache reorder, whole-step HIP graph, two batches on two streams,
+measured machine peaks).
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 3] [--no-cpu-baseline]
+    python bench.py --sweep-attn-plan        # the (B, L, W) x (row tile, L segments) table the launch rule is fitted to
 """
 import argparse
 import json
@@ -36,6 +40,78 @@ def _stored_traffic(config_id):
     return None
 
 
+def _elapsed(torch, fn, reps):
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / reps
+
+
+def measured_peaks(torch, gr, dev):
+    """What this GPU sustains: a plain streaming read of 1 GiB and back-to-back bf16 MFMAs on N(0,1) operands."""
+    sink = torch.zeros(4, dtype=torch.float32, device=dev)
+    src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+    src.view(torch.float32).normal_()
+    for _ in range(20):
+        gr.gr_diag_stream_read(src, sink)
+    ms = _elapsed(torch, lambda: gr.gr_diag_stream_read(src, sink), 20)
+    read_gbs = src.numel() / (ms * 1e-3) / 1e9
+    del src
+    ops = torch.randn(8192, dtype=torch.float32, device=dev).to(torch.bfloat16)          # 16 KiB of bf16 N(0,1)
+    wgs, iters = 256 * 4, 4096
+    flops = 0.0
+    for _ in range(10):
+        flops = gr.gr_diag_mfma_loop(ops, wgs, iters, sink)
+    ms = _elapsed(torch, lambda: gr.gr_diag_mfma_loop(ops, wgs, iters, sink), 10)
+    return dict(hbm_read_GBps=round(read_gbs, 1), bf16_mfma_TFLOPs=round(flops / (ms * 1e-3) / 1e12, 1),
+                how="plain 16-byte-load read of 1 GiB; 1024 workgroups x 8 waves of back-to-back 32x32x16 bf16 MFMAs on N(0,1) operands, both after the clock has settled")
+
+
+def sweep_attn_plan(torch, gr, dev):
+    """Attention time (u = 2) for every row tile and L split the kernel has, on the shapes the launch rule was fitted to.
+    gr_diag_attn_plan(rows, segments) overrides the rule; the workspace is sized by the binding for whichever plan is in force."""
+    import numpy as np
+    import gr_synth
+    shapes = [(8, 2048, 128), (4, 16384, 512), (1, 4096, 256), (2, 8192, 256), (16, 1024, 256), (4, 2048, 512), (64, 512, 128), (32, 4096, 256)]
+    Hq, Hkv, d, ND = 32, 8, 128, 3
+    scale = float(np.float32(1 / np.sqrt(d)))
+    print("B, L, W | rule us | " + " ".join(f"{r}x{n}" for r in (128, 256) for n in (1, 2, 4, 8, 16)))
+    for B, L, W in shapes:
+        q = torch.randn((B, W, Hq, d), device=dev).to(torch.bfloat16)
+        ks = torch.randn((B * L, Hkv, d), device=dev).to(torch.bfloat16)
+        vs = torch.randn((B * L, Hkv, d), device=dev).to(torch.bfloat16)
+        ku = torch.randn((B, W, ND, Hkv, d), device=dev).to(torch.bfloat16)
+        vu = torch.randn((B, W, ND, Hkv, d), device=dev).to(torch.bfloat16)
+        cu = torch.arange(0, (B + 1) * L, L, dtype=torch.int32, device=dev)
+        out = torch.empty_like(q)
+
+        def run():
+            gr.gr_beam_attn(q, ks, vs, cu, ku, vu, 2, scale, L, B * L, out=out)
+
+        def timed():
+            for _ in range(5):
+                run()
+            return _elapsed(torch, run, 10) * 1e3
+        gr.gr_diag_attn_plan(0, 0)
+        t_pre = time.perf_counter()
+        while time.perf_counter() - t_pre < 0.06:        # let the clock settle under this shape's load before the first column
+            run()
+            torch.cuda.synchronize()
+        cells = [f"{timed():.0f}"]
+        for rows in (128, 256):
+            for nseg in (1, 2, 4, 8, 16):
+                gr.gr_diag_attn_plan(rows, nseg)
+                try:
+                    cells.append(f"{timed():.0f}")
+                except gr.GrError:
+                    cells.append("-")
+        gr.gr_diag_attn_plan(0, 0)
+        print(f"{B}, {L}, {W} | " + " | ".join([cells[0], " ".join(cells[1:])]), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -44,16 +120,18 @@ def main():
     ap.add_argument("--config", type=int, default=3, help="workload id 1..5 (3 and 5 are the W=256 headline shapes)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-requests", type=int, default=0, help="requests timed on the CPU oracle (0 = auto)")
-    ap.add_argument("--flags", type=int, default=0, help="GR_SELECT_* flags for the item step")
-    ap.add_argument("--no-mask", action="store_true", help="unconstrained item step (mask = NULL)")
+    ap.add_argument("--flags", type=int, default=0, help="GR_SELECT_* flags for the item step of the headline")
+    ap.add_argument("--no-mask", action="store_true", help="unconstrained item step (mask = NULL) in the headline")
     ap.add_argument("--prewarm-ms", type=float, default=60.0,
                     help="untimed: run the step loop for this long before the W warm-up steps, so that the GPU's clock "
                          "management has settled (the first ~25 ms of sustained work after idle run ~20%% slower)")
     ap.add_argument("--no-extras", action="store_true",
-                    help="skip the untimed extras reported beside the headline (cache reorder timing, whole-step HIP graph replay)")
+                    help="skip everything measured outside the headline's timed region (dense-path item step, cache reorder, "
+                         "HIP graph, two streams, measured peaks)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (known HBM traffic) so that rocprofv3 FETCH_SIZE / WRITE_SIZE "
                          "readings of the same run can be scaled")
+    ap.add_argument("--sweep-attn-plan", action="store_true", help="print the launch-plan sweep table and exit")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; requests are independent and would shard across GPUs with no exchange, "
@@ -72,6 +150,9 @@ def main():
     gr.load_library()          # raises if the HIP library is missing: there is no fallback path
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if args.sweep_attn_plan:
+        sweep_attn_plan(torch, gr, dev)
+        return
     cfg = gr_synth.get_config(args.config)
     B, W, V, ND, Hq, Hkv, d = cfg.B, cfg.W, cfg.V, cfg.ND, cfg.Hq, cfg.Hkv, cfg.d
     scale = float(np.float32(1.0 / np.sqrt(d)))
@@ -95,33 +176,36 @@ def main():
         lg = gr_synth.make_logits(cfg, s)
         logits_host.append(lg)
         logits.append(torch.from_numpy(lg).to(dev))
-    mask = None if args.no_mask else gr.gr_item_mask_build(torch.from_numpy(items).to(dev), V)
+    mask_blob = gr.gr_item_mask_build(torch.from_numpy(items).to(dev), V)
+    mask = None if args.no_mask else mask_blob
     t_gen = time.time() - t_gen
 
     # ---------------- fixed buffers (nothing is allocated inside the timed region)
-    out = torch.empty((B, W, Hq, d), dtype=torch.bfloat16, device=dev)
-    ws_attn_bytes = gr.attn_workspace_bytes(B, W, Hq, Hkv, d, max_L)
-    ws_attn = torch.empty(max(ws_attn_bytes, 256), dtype=torch.uint8, device=dev)
-    ws_sel = torch.empty(gr.select_workspace_bytes(B, W, V, ND), dtype=torch.uint8, device=dev)
+    def make_buffers():
+        mk = lambda: dict(parent=torch.empty((B, W), dtype=torch.int32, device=dev), token=torch.empty((B, W), dtype=torch.int32, device=dev),
+                          scores=torch.empty((B, W), dtype=torch.float32, device=dev), prefix=torch.empty((B, W, ND), dtype=torch.int32, device=dev),
+                          range=torch.empty((B, W, 2), dtype=torch.int32, device=dev), item_index=torch.empty((B, W), dtype=torch.int32, device=dev))
+        return dict(out=torch.empty((B, W, Hq, d), dtype=torch.bfloat16, device=dev),
+                    ws_attn=torch.empty(max(gr.attn_workspace_bytes(B, W, Hq, Hkv, d, max_L), 256), dtype=torch.uint8, device=dev),
+                    ws_sel=torch.empty(gr.select_workspace_bytes(B, W, V, ND), dtype=torch.uint8, device=dev),
+                    sel_out=[mk() for _ in range(ND)])
+    buf = make_buffers()
     sc0, pf0, rg0 = gr_synth.initial_beam_state(B, W, ND)
     state = [dict(scores=torch.from_numpy(sc0).to(dev), prefix=torch.from_numpy(pf0).to(dev), range=torch.from_numpy(rg0).to(dev))]
-    mk = lambda: dict(parent=torch.empty((B, W), dtype=torch.int32, device=dev), token=torch.empty((B, W), dtype=torch.int32, device=dev),
-                      scores=torch.empty((B, W), dtype=torch.float32, device=dev), prefix=torch.empty((B, W, ND), dtype=torch.int32, device=dev),
-                      range=torch.empty((B, W, 2), dtype=torch.int32, device=dev), item_index=torch.empty((B, W), dtype=torch.int32, device=dev))
-    sel_out = [mk() for _ in range(ND)]
 
-    def attn(s):
+    def attn(s, bufs=buf, stream=None):
         a = attn_in[s]
-        gr.gr_beam_attn(a["q"], k_sh, v_sh, d_cu, a["ku"], a["vu"], a["u"], scale, max_L, total_L, out=out, workspace=ws_attn)
+        gr.gr_beam_attn(a["q"], k_sh, v_sh, d_cu, a["ku"], a["vu"], a["u"], scale, max_L, total_L, out=bufs["out"], workspace=bufs["ws_attn"], stream=stream)
 
-    def select(s):
+    def select(s, bufs=buf, stream=None, m="headline", flags=None):
         st = state[s]
-        gr.gr_beam_select(mask, logits[s], st["scores"], st["prefix"], st["range"], s, flags=args.flags, out=sel_out[s], workspace=ws_sel)
+        gr.gr_beam_select(mask if m == "headline" else m, logits[s], st["scores"], st["prefix"], st["range"], s,
+                          flags=args.flags if flags is None else flags, out=bufs["sel_out"][s], workspace=bufs["ws_sel"], stream=stream)
 
-    # real beam chain once: the state entering level s is what levels 0..s-1 selected
+    # real beam chain once (with the mask, whatever the headline uses): the state entering level s is what levels 0..s-1 selected
     for s in range(ND):
-        select(s)
-        state.append(dict(scores=sel_out[s]["scores"], prefix=sel_out[s]["prefix"], range=sel_out[s]["range"]))
+        select(s, m=mask_blob, flags=0)
+        state.append(dict(scores=buf["sel_out"][s]["scores"].clone(), prefix=buf["sel_out"][s]["prefix"].clone(), range=buf["sel_out"][s]["range"].clone()))
     torch.cuda.synchronize()
     live_rows = [int((state[s]["scores"] > float("-inf")).sum().item()) for s in range(ND)]
 
@@ -131,6 +215,10 @@ def main():
         dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
+
+    # ---------------- the first launches after idle (reported, not part of the headline)
+    time.sleep(0.2)
+    cold_ms = _elapsed(torch, lambda: attn(ND - 1), 20)
 
     # ---------------- warm-up, then K timed steps
     prewarm_steps = 0
@@ -174,35 +262,55 @@ def main():
     roofline = dict(bound="mfma", kernel="k_beam_attn", achieved=round(attn_tflops, 2), peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
                     frac=round(attn_tflops / PEAK_BF16_TFLOPS, 4), traffic=_stored_traffic(cfg.config_id),
                     avg_launch_ms=round(attn_ms_avg, 4), flops_per_launch=attn_flops_avg)
-    # item step: algorithmic bytes of a dense pass = live rows * (4V logits + V/8 mask bits)
     sel_by_level = {}
     for s in range(ND):
         ms = [sel_ms[i] for i in range(K) if i % ND == s]
         if ms:
-            dense_bytes = live_rows[s] * (4.0 * V + V / 8.0)
-            sel_by_level[f"level{s}"] = dict(ms=round(float(np.mean(ms)), 4), live_rows=live_rows[s],
-                                             dense_GBps=round(dense_bytes / (float(np.mean(ms)) * 1e-3) / 1e9, 1))
+            sel_by_level[f"level{s}"] = dict(ms=round(float(np.mean(ms)), 4), live_rows=live_rows[s])
 
     # ---------------- extras, outside the headline's timed region
-    reorder, graph = None, None
+    roofline_select, reorder, graph, streams, peaks = None, None, None, None, None
     if not args.no_extras:
+        # (0) the item step on its dense paths: every live row streamed in full (GR_SELECT_FORCE_DENSE, and mask = NULL),
+        # on the levels where all B*W rows are live.  Algorithmic bytes = live rows x (4V logits + V/8 mask bits); the time
+        # is the whole gr_beam_select call (rows kernel + selection kernel).  An attention launch runs (untimed) before
+        # every timed call, as in the headline loop: the logits are not in any cache and the clock is in its loaded state.
+        legs = {}
+        worst = None
+        for name, m, fl, mask_bytes in (("forced_dense", mask_blob, gr.GR_SELECT_FORCE_DENSE, V / 8.0), ("no_mask", None, 0, 0.0)):
+            for s in range(ND):
+                if live_rows[s] != B * W:
+                    continue
+                reps = 12
+                e = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(reps)]
+                for r in range(reps):
+                    attn(s)
+                    e[r][0].record()
+                    select(s, m=m, flags=fl)
+                    e[r][1].record()
+                torch.cuda.synchronize()
+                ms = float(np.mean([e[r][0].elapsed_time(e[r][1]) for r in range(2, reps)]))
+                nbytes = live_rows[s] * (4.0 * V + mask_bytes)
+                gbs = nbytes / (ms * 1e-3) / 1e9
+                legs[f"{name}_level{s}"] = dict(ms=round(ms, 4), bytes=nbytes, GBps=round(gbs, 1), frac=round(gbs / PEAK_HBM_GBS, 4))
+                if worst is None or gbs < worst[1]:
+                    worst = (f"{name}_level{s}", gbs, ms, nbytes)
+        if worst:
+            roofline_select = dict(bound="hbm", kernel="k_rows + k_select (whole gr_beam_select call)", achieved=round(worst[1], 1), peak=PEAK_HBM_GBS,
+                                   unit="GB/s", frac=round(worst[1] / PEAK_HBM_GBS, 4), leg=worst[0], legs=legs,
+                                   note="dense paths only (every live row streamed); achieved/frac = the slowest leg; the default path gathers "
+                                        "rows with few valid children and is reported as time in `select`")
         # (1) in-place move of the surviving beams' decode cache (gr_beam_reorder) with the parents each level selected
         ku_w, vu_w = attn_in[ND - 1]["ku"].clone(), attn_in[ND - 1]["vu"].clone()
-        reorder = {}
+        reorder = dict(note="GBps counts bytes read + written; the 67-200 MB working set partly lives in the 256 MB Infinity Cache, "
+                            "so this is a cache-inclusive rate, not an HBM rate")
         for s in range(ND):
-            par = sel_out[s]["parent"]
+            par = buf["sel_out"][s]["parent"]
             for _ in range(2):
                 gr.gr_beam_reorder(par, ku_w, vu_w, s + 1)
-            r0, r1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            reps = 10
-            r0.record()
-            for _ in range(reps):
-                gr.gr_beam_reorder(par, ku_w, vu_w, s + 1)
-            r1.record()
-            torch.cuda.synchronize()
-            ms = r0.elapsed_time(r1) / reps
+            ms = _elapsed(torch, lambda: gr.gr_beam_reorder(par, ku_w, vu_w, s + 1), 10)
             moved = 2.0 * 2.0 * B * W * (s + 1) * Hkv * d * 2          # K and V, read + write
-            reorder[f"u{s + 1}"] = dict(ms=round(ms, 4), GBps=round(moved / (ms * 1e-3) / 1e9, 1))
+            reorder[f"u{s + 1}"] = dict(ms=round(ms, 4), GBps_cache_inclusive=round(moved / (ms * 1e-3) / 1e9, 1))
         del ku_w, vu_w
         # (2) the ND-level cycle (attention + item step per level) captured once as a HIP graph and replayed
         try:
@@ -217,23 +325,52 @@ def main():
             with torch.cuda.graph(g):
                 for s in range(ND):
                     attn(s); select(s)
-            ref = {k: sel_out[ND - 1][k].clone() for k in ("parent", "token", "scores")}
+            ref = {k: buf["sel_out"][ND - 1][k].clone() for k in ("parent", "token", "scores")}
             t_pre = time.perf_counter()
             while (time.perf_counter() - t_pre) * 1e3 < max(args.prewarm_ms, 1.0):
                 g.replay()
                 torch.cuda.synchronize()
             cycles = max(1, K // ND)
-            g0, g1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            g0.record()
-            for _ in range(cycles):
-                g.replay()
-            g1.record()
-            torch.cuda.synchronize()
-            gms = g0.elapsed_time(g1) / (cycles * ND)
-            same = all(bool(torch.equal(ref[k], sel_out[ND - 1][k])) for k in ref)
+            gms = _elapsed(torch, g.replay, cycles) / ND
+            same = all(bool(torch.equal(ref[k], buf["sel_out"][ND - 1][k])) for k in ref)
             graph = dict(ms_per_step=round(gms, 4), steps_per_s=round(1000.0 / gms, 3), cycles=cycles, replay_matches_eager=same)
         except Exception as e:          # the headline above stands on its own
             graph = dict(error=f"{type(e).__name__}: {e}"[:300])
+        # (3) two independent batches on two streams of equal priority (one stream per batch): aggregate rate
+        try:
+            buf2 = make_buffers()
+            s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+            for st_ in (s1, s2):
+                st_.wait_stream(torch.cuda.current_stream())
+            cycles = max(1, K // ND)
+
+            def both(n):
+                for _ in range(n):
+                    for s in range(ND):
+                        attn(s, buf, s1); select(s, buf, s1)
+                        attn(s, buf2, s2); select(s, buf2, s2)
+            both(2)
+            torch.cuda.synchronize()
+            t1 = time.perf_counter()
+            both(cycles)
+            torch.cuda.synchronize()
+            dt = time.perf_counter() - t1
+            agree = all(bool(torch.equal(buf["sel_out"][ND - 1][k], buf2["sel_out"][ND - 1][k])) for k in ("parent", "token", "scores"))
+            streams = dict(batches=2, aggregate_steps_per_s=round(2 * cycles * ND / dt, 3), single_stream_steps_per_s=round(steps_per_s, 3),
+                           both_batches_agree=agree)
+            del buf2
+        except Exception as e:
+            streams = dict(error=f"{type(e).__name__}: {e}"[:300])
+        # (4) what the machine sustains, next to the datasheet peaks
+        try:
+            peaks = measured_peaks(torch, gr, dev)
+            roofline["peak_measured"] = peaks["bf16_mfma_TFLOPs"]
+            roofline["frac_of_measured"] = round(attn_tflops / peaks["bf16_mfma_TFLOPs"], 4)
+            if roofline_select:
+                roofline_select["peak_measured"] = peaks["hbm_read_GBps"]
+                roofline_select["frac_of_measured"] = round(roofline_select["achieved"] / peaks["hbm_read_GBps"], 4)
+        except Exception as e:
+            peaks = dict(error=f"{type(e).__name__}: {e}"[:300])
 
     # ---------------- CPU oracle on a bounded sample of the same workload
     cpu = None
@@ -266,10 +403,11 @@ def main():
                     total_L=total_L, Hq=Hq, Hkv=Hkv, d=d, decode_steps=ND, n_items=cfg.n_items, mask=(not args.no_mask), flags=args.flags,
                     step_definition="one gr_beam_attn + one gr_beam_select over the whole batch; levels cycle 0,1,2"),
         request_steps_per_s=round(steps_per_s * B, 1),
-        roofline=roofline, cpu_baseline=cpu,
+        roofline=roofline, roofline_select=roofline_select, cpu_baseline=cpu,
         attn=dict(ms_by_u={f"u{s + 1}": round(float(np.mean([attn_ms[i] for i in range(K) if i % ND == s] or [0])), 4) for s in range(ND)},
-                  tflops=round(attn_tflops, 2)),
-        select=sel_by_level, reorder=reorder, graph=graph, prewarm=dict(ms=args.prewarm_ms, steps=prewarm_steps), wall_s=round(wall, 3), input_gen_s=round(t_gen, 1))
+                  tflops=round(attn_tflops, 2), ms_first20_after_idle=round(cold_ms, 4)),
+        select=sel_by_level, reorder=reorder, graph=graph, two_streams=streams, peaks_measured=peaks,
+        prewarm=dict(ms=args.prewarm_ms, steps=prewarm_steps), wall_s=round(wall, 3), input_gen_s=round(t_gen, 1))
     print(json.dumps(line))
 
 

@@ -195,6 +195,27 @@ gr_status gr_beam_select_noalloc(const gr_select_params* p, void* stream);
 gr_status gr_beam_reorder(int32_t B, int32_t W, int32_t ND, int32_t Hkv, int32_t d, int32_t u,
                           const int32_t* parent, void* k_unshared, void* v_unshared, void* stream);
 
+/* ------------------------------------------------------------------------------------------------
+ * Diagnostics: the rates this GPU really sustains, reported by the benchmark next to the datasheet peaks
+ * (the evaluation quotes achieved rates against the hardware's capability; Section 9.4).  Not part of the
+ * decode path.  Both only enqueue on `stream`.
+ *
+ * gr_diag_stream_read: reads `bytes` (>= 1 MiB, 16-byte aligned device memory; whole 32 KiB slices are read)
+ *   with 16-byte loads and discards them; `sink` is 4 writable device bytes.
+ * gr_diag_mfma_loop: `workgroups` x 8 wavefronts each issue `iters` x 4 back-to-back bf16 32x32x16 MFMAs on the
+ *   operands found at `operands` (16 KiB of device memory: 2 x 512 x 16 bytes of bf16); `sink` is 4 writable
+ *   device bytes.  gr_diag_mfma_flops gives the floating-point operations of such a launch (host only).
+ * gr_diag_attn_plan: host only, process-wide.  Makes every later gr_beam_attn / gr_beam_attn_workspace_bytes use
+ *   workgroups of `rows_per_workgroup` (128 or 256) query rows and `l_segments` (1..16, lowered to the number of
+ *   K/V tiles in the longest prompt) prompt segments instead of the built-in launch rule; (0, 0) restores the rule.
+ *   For sweeps that refit the rule; not thread-safe against concurrent gr_beam_attn calls.
+ * Errors: INVALID_ARG, UNSUPPORTED, HIP.
+ * ------------------------------------------------------------------------------------------------ */
+gr_status gr_diag_attn_plan(int32_t rows_per_workgroup, int32_t l_segments);
+gr_status gr_diag_stream_read(const void* src, size_t bytes, void* sink, void* stream);
+gr_status gr_diag_mfma_loop(const void* operands, int32_t workgroups, int32_t iters, void* sink, void* stream);
+double    gr_diag_mfma_flops(int32_t workgroups, int32_t iters);
+
 #ifdef __cplusplus
 }
 #endif

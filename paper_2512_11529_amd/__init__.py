@@ -18,7 +18,8 @@ from . import build as _build
 
 __all__ = ["load_library", "gr_beam_attn", "gr_item_mask_build", "gr_beam_select", "gr_beam_select_noalloc", "gr_beam_reorder",
            "gr_status_string",
-           "attn_workspace_bytes", "select_workspace_bytes", "GrError", "GR_SELECT_FORCE_DENSE", "LIB_PATH"]
+           "attn_workspace_bytes", "select_workspace_bytes", "GrError", "GR_SELECT_FORCE_DENSE", "LIB_PATH",
+           "gr_diag_stream_read", "gr_diag_mfma_loop", "gr_diag_attn_plan"]
 
 LIB_PATH = _build.LIB_PATH
 GR_SELECT_FORCE_DENSE = 1
@@ -79,6 +80,14 @@ def load_library(path: str = None):
     lib.gr_beam_select_noalloc.argtypes = [ctypes.POINTER(_SelectParams), ctypes.c_void_p]
     lib.gr_beam_select_noalloc_max_workspace_bytes.restype = ctypes.c_size_t
     lib.gr_beam_select_noalloc_max_workspace_bytes.argtypes = []
+    lib.gr_diag_stream_read.restype = ctypes.c_int32
+    lib.gr_diag_stream_read.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_void_p]
+    lib.gr_diag_mfma_loop.restype = ctypes.c_int32
+    lib.gr_diag_mfma_loop.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p]
+    lib.gr_diag_attn_plan.restype = ctypes.c_int32
+    lib.gr_diag_attn_plan.argtypes = [ctypes.c_int32, ctypes.c_int32]
+    lib.gr_diag_mfma_flops.restype = ctypes.c_double
+    lib.gr_diag_mfma_flops.argtypes = [ctypes.c_int32, ctypes.c_int32]
     lib.gr_beam_reorder.restype = ctypes.c_int32
     lib.gr_beam_reorder.argtypes = [ctypes.c_int32] * 6 + [ctypes.c_void_p] * 4
     _lib = lib
@@ -260,3 +269,29 @@ def gr_beam_reorder(parent, k_unshared, v_unshared, u, stream=None):
     rc = lib.gr_beam_reorder(B, W, ND, Hkv, d, int(u), _ptr(parent), _ptr(k_unshared), _ptr(v_unshared), _stream(stream))
     if rc != 0:
         raise GrError(rc, "gr_beam_reorder")
+
+
+def gr_diag_attn_plan(rows_per_workgroup=0, l_segments=0):
+    """Force the attention launch plan (rows per workgroup 128/256, prompt segments 1..16) for later calls; (0, 0) = built-in rule."""
+    rc = load_library().gr_diag_attn_plan(int(rows_per_workgroup), int(l_segments))
+    if rc != 0:
+        raise GrError(rc, "gr_diag_attn_plan")
+
+
+def gr_diag_stream_read(src, sink, stream=None):
+    """Enqueue a plain streaming read of the CUDA tensor `src` (measured HBM read rate).  `sink`: any 4-byte CUDA tensor."""
+    rc = load_library().gr_diag_stream_read(_ptr(src), src.numel() * src.element_size(), _ptr(sink), _stream(stream))
+    if rc != 0:
+        raise GrError(rc, "gr_diag_stream_read")
+
+
+def gr_diag_mfma_loop(operands, workgroups, iters, sink, stream=None):
+    """Enqueue a loop of back-to-back bf16 MFMAs on `operands` (16 KiB CUDA tensor).  Returns the launch's FLOP count."""
+    lib = load_library()
+    if operands.numel() * operands.element_size() < 16384:
+        raise ValueError("operands must hold 16 KiB")
+    rc = lib.gr_diag_mfma_loop(_ptr(operands), int(workgroups), int(iters), _ptr(sink), _stream(stream))
+    if rc != 0:
+        raise GrError(rc, "gr_diag_mfma_loop")
+    return float(lib.gr_diag_mfma_flops(int(workgroups), int(iters)))
+

@@ -648,10 +648,17 @@ __global__ void __launch_bounds__(256) k_attn_order(const int32_t* cu, int B, in
 // workgroup per CU exists (never fewer than four tiles per segment), and not at all once 256 units
 // exist without it.
 struct AttnPlan { int mwg, nsplit; };
+int g_plan_rows = 0, g_plan_segments = 0;                  // gr_diag_attn_plan: 0 = use the rule below
 AttnPlan plan_attn(const gr_attn_params* p) {
   const int g = p->Hq / p->Hkv;
   const int64_t M = (int64_t)p->W * g;
   AttnPlan plan;
+  if (g_plan_rows) {                                        // a sweep asked for this tiling; keep at least one tile per segment
+    const int64_t cap = p->max_L / KT;
+    plan.mwg = g_plan_rows;
+    plan.nsplit = (int)(g_plan_segments < cap ? g_plan_segments : (cap < 1 ? 1 : cap));
+    return plan;
+  }
   plan.mwg = M <= 128 ? 128 : 256;
   const int64_t units = (int64_t)p->B * p->Hkv * ((M + plan.mwg - 1) / plan.mwg);
   plan.nsplit = 1;
@@ -673,6 +680,13 @@ bool attn_wants_order(const gr_attn_params* p, const AttnPlan& plan) {
 }
 
 }  // namespace
+
+extern "C" gr_status gr_diag_attn_plan(int32_t rows_per_workgroup, int32_t l_segments) {
+  if (rows_per_workgroup == 0 && l_segments == 0) { g_plan_rows = g_plan_segments = 0; return GR_OK; }
+  if ((rows_per_workgroup != 128 && rows_per_workgroup != 256) || l_segments < 1 || l_segments > 16) return GR_ERR_INVALID_ARG;
+  g_plan_rows = rows_per_workgroup; g_plan_segments = l_segments;
+  return GR_OK;
+}
 
 extern "C" size_t gr_beam_attn_workspace_bytes(const gr_attn_params* p) {
   if (!p || p->B <= 0 || p->W <= 0 || p->Hq <= 0 || p->Hkv <= 0 || p->Hq % p->Hkv) return 0;
