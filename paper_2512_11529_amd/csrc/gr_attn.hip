@@ -66,7 +66,10 @@ __device__ __forceinline__ void divmod_small(int n, int d, float rcp_d, int* q, 
 template <int D, int NCB>
 struct AttnTile {
   static constexpr int KSTR = D + 8;     // K rows: +16 B  -> ds_read_b128 of 32 consecutive rows is conflict-free
-  static constexpr int VSTR = D + 16;    // V rows: +32 B  -> ds_read_b64_tr_b16 of 4-row groups is conflict-free
+  // V rows: +64 B.  One ds_read_b64_tr_b16 serves 32 lanes per cycle = 4 rows x 2 column halves x 32 bytes; a row
+  // stride of 64 B modulo 256 B puts those eight 32-byte groups on eight different bank groups (with +32 B the
+  // second half of row r and the first half of row r+1 share banks: a 2-way conflict on every V operand read).
+  static constexpr int VSTR = D + 32;
 
   // S^T = K . Q^T from the K tile in LDS (A operand) and Q in registers (B operand)
   static __device__ __forceinline__ void qk(const uint16_t* sk, const bf16x8 (&qop)[NCB][D / 16], f32x16 (&s)[KT / 32][NCB],
@@ -127,6 +130,91 @@ struct AttnTile {
       __builtin_amdgcn_sched_group_barrier(0x100, 2, 1);
     }
     __builtin_amdgcn_sched_group_barrier(0x008, PF * NCB, 1);
+  }
+
+  // Per-lane maximum of a tile's scores for the lane's query column (both halves of the column).
+  static __device__ __forceinline__ float colmax(const f32x16 (&s)[KT / 32][NCB]) {
+    float mx = -INFINITY;
+#pragma unroll
+    for (int sub = 0; sub < KT / 32; sub++)
+#pragma unroll
+      for (int i = 0; i < 16; i += 2) mx = fmaxf(fmaxf(mx, s[sub][0][i]), s[sub][0][i + 1]);
+    return fmaxf(mx, __shfl_xor(mx, 32, 64));
+  }
+
+  // One steady-state tile with the matrix and vector pipes kept busy together.  The wave issues, in this order,
+  // the MFMAs of S(t+1) = K(t+1).Q^T and then those of O += V(t).P(t); between consecutive MFMAs it
+  // exponentiates a fixed share of tile t's scores (reference maximum already decided: mc = m_ref * c), so that
+  // the 32 quarter-rate exponentials per lane run in the shadow of the 32 MFMAs instead of after them.  P(t) is
+  // complete before the second half of the PV MFMAs starts; those are interleaved with the column maximum of
+  // S(t+1), which the next tile's decision needs.  Instruction order is pinned chunk by chunk.
+  static constexpr int NQK = (KT / 32) * (D / 16), NPV = (KT / 16) * (D / 32), NMF = NQK + NPV;
+  static constexpr int EXP_BY = NQK + NPV / 2;            // all 32 exponentials are done after this many MFMAs
+  static constexpr int exps_after(int j) {                // exponentials finished once MFMA j's chunk has been issued
+    const int t = (32 * (j + 1) + EXP_BY - 1) / EXP_BY;
+    return j < 0 ? 0 : (t > 32 ? 32 : t);
+  }
+  static __device__ __forceinline__ void fused(const uint16_t* sk_next, const uint16_t* sv_cur, const bf16x8 (&qop)[NCB][D / 16],
+                                               const f32x16 (&s_cur)[KT / 32][NCB], f32x16 (&s_next)[KT / 32][NCB],
+                                               f32x16 (&o)[D / 32][NCB], float mc, float c, float& l_run, float& mx_next, int lane) {
+    static_assert(NCB == 1, "one column block per wave");
+    typedef short s16x8 __attribute__((ext_vector_type(8)));
+    const int G = lane >> 5, n32 = lane & 31;
+    const uint16_t* kb = sk_next + n32 * KSTR + G * 8;
+    const uint16_t* vb = sv_cur + (4 * G + ((lane & 15) >> 2)) * VSTR + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+    auto rdk = [&](int i) { return as_bf16x8(*(const uint4*)(kb + (i % 2) * 32 * KSTR + (i / 2) * 16)); };
+    auto rdv = [&](int i) {
+      const uint16_t* p0 = vb + (i / (D / 32)) * 16 * VSTR + (i % (D / 32)) * 32;
+      s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p0));
+      s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p0 + 8 * VSTR));
+      s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+      return __builtin_bit_cast(bf16x8, both);
+    };
+    constexpr int PF = 4;                                   // operand reads run PF MFMAs ahead
+    constexpr int SCAN0 = NMF - NPV / 2, EPC = 32 / (NPV / 2);   // maximum scan: EPC scores per chunk from MFMA SCAN0 on
+    bf16x8 a[NMF];
+    bf16x8 pop[KT / 16];
+    float p[8];
+    float rs = 0.f, mx = -INFINITY;
+    const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int i = 0; i < PF; i++) a[i] = rdk(i);
+#pragma unroll
+    for (int j = 0; j < NMF; j++) {
+      if (j + PF < NMF) a[j + PF] = (j + PF < NQK) ? rdk(j + PF) : rdv(j + PF - NQK);
+      if (j < NQK) {
+        s_next[j % 2][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[j], qop[0][j / 2], j < 2 ? zero : s_next[j % 2][0], 0, 0, 0);
+      } else {
+        const int i = j - NQK;
+        o[i % (D / 32)][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[j], pop[i / (D / 32)], o[i % (D / 32)][0], 0, 0, 0);
+      }
+#pragma unroll
+      for (int e = exps_after(j - 1); e < exps_after(j); e++) {
+        const float v = __builtin_amdgcn_exp2f(fmaf(s_cur[e / 16][0][e % 16], c, -mc));
+        rs += v;
+        p[e % 8] = v;
+        if (e % 8 == 7) {
+          bf16x8 pk;
+#pragma unroll
+          for (int k = 0; k < 8; k += 2) {
+            f32x2 two = {p[k], p[k + 1]};
+            bf16x2 h = __builtin_convertvector(two, bf16x2);
+            pk[k] = h[0];
+            pk[k + 1] = h[1];
+          }
+          pop[e / 8] = pk;
+        }
+      }
+      if (j >= SCAN0) {
+#pragma unroll
+        for (int e = (j - SCAN0) * EPC; e < (j - SCAN0 + 1) * EPC; e += 2)
+          mx = fmaxf(fmaxf(mx, s_next[e / 16][0][e % 16]), s_next[e / 16][0][e % 16 + 1]);
+      }
+      asm volatile("" : "+v"(rs), "+v"(mx));                 // the running sum and maximum are due here, not at the end of the tile
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    l_run += rs;
+    mx_next = fmaxf(mx, __shfl_xor(mx, 32, 64));
   }
 
   // Online softmax of one tile, one query column per lane (its other half lives in lane^32).
@@ -375,20 +463,27 @@ k_beam_attn(AttnCtx c) {
             for (int i = 0; i < 16; i++) o_acc[db][cb][i] *= alpha[cb];
         }
     };
-    // one steady-state iteration: tile t (scores in s_in) has a successor whose scores go to s_out
+    // one steady-state iteration: tile t (scores in s_in, column maxima in mx_cur) has a successor whose scores
+    // go to s_out.  The reference maximum is settled first (raising it, and rescaling O and the running sum, is a
+    // rare wave-uniform branch), so that the tile's MFMAs and exponentials form one straight-line block.
+    float mx_cur = -INFINITY;
     auto step = [&](f32x16 (&s_in)[KT / 32][NCB], f32x16 (&s_out)[KT / 32][NCB], int t) {
+      if (__any(mx_cur * c.c > m_run[0] * c.c + T::kLazy)) {
+        const float m_new = fmaxf(m_run[0], mx_cur);
+        const float alpha = __builtin_amdgcn_exp2f((m_run[0] - m_new) * c.c);
+#pragma unroll
+        for (int db = 0; db < D / 32; db++)
+#pragma unroll
+          for (int i = 0; i < 16; i++) o_acc[db][0][i] *= alpha;
+        l_run[0] *= alpha;
+        m_run[0] = m_new;
+      }
       __syncthreads();
       lstore(s_k + (t & 1) * KT * KSTR, KSTR, kreg);                 // K(t+2)
       lstore(s_v + ((t + 1) & 1) * KT * VSTR, VSTR, vreg);           // V(t+1)
       kreg = gload(kbase, min(t + 3, tl));
       vreg = gload(vbase, min(t + 2, tl));
-      bf16x8 pop[KT / 16][NCB];
-      float alpha[NCB];
-      bool upd[NCB];
-      T::qk(s_k + ((t + 1) & 1) * KT * KSTR, qop, s_out, n32, G);
-      T::softmax(s_in, pop, m_run, l_run, alpha, upd, c.c);
-      rescale(alpha, upd);
-      T::pv(s_v + (t & 1) * KT * VSTR, pop, o_acc, lane);
+      T::fused(s_k + ((t + 1) & 1) * KT * KSTR, s_v + (t & 1) * KT * VSTR, qop, s_in, s_out, o_acc, m_run[0] * c.c, c.c, l_run[0], mx_cur, lane);
     };
     // the last tile of the segment: the only one that can be partial, and it has no successor
     auto last = [&](f32x16 (&s_in)[KT / 32][NCB], int t) {
@@ -415,6 +510,7 @@ k_beam_attn(AttnCtx c) {
 
     f32x16 s_a[KT / 32][NCB], s_b[KT / 32][NCB];      // ping-pong score accumulators: no copies
     T::qk(s_k, qop, s_a, n32, G);
+    if (ntiles > 1) mx_cur = T::colmax(s_a);
     // ntiles - 1 steps, then the last tile.  An odd step is peeled off first so that the loop runs
     // whole ping-pong pairs and the last tile is always in s_a.
     int t = 0;
@@ -749,8 +845,8 @@ extern "C" gr_status gr_beam_attn(const gr_attn_params* p, void* workspace, size
   const int64_t groups_padded = ((int64_t)c.n_groups + 7) / 8 * 8;
   const int64_t grid = groups_padded * c.MB;
   if (grid >= ((int64_t)1 << 31)) return GR_ERR_UNSUPPORTED;
-  const size_t lds_tiles = (size_t)2 * KT * ((p->d + 8) + (p->d + 16)) * 2;            // K and V tiles, double-buffered, padded rows
-  const size_t lds_own = (size_t)(plan.mwg / 32) * 32 * ((p->d + 8) + (p->d + 16)) * 2;  // one 32-row K and V mini-tile per wave
+  const size_t lds_tiles = (size_t)2 * KT * ((p->d + 8) + (p->d + 32)) * 2;            // K and V tiles, double-buffered, padded rows
+  const size_t lds_own = (size_t)(plan.mwg / 32) * 32 * ((p->d + 8) + (p->d + 32)) * 2;  // one 32-row K and V mini-tile per wave
   const size_t lds = lds_tiles > lds_own ? lds_tiles : lds_own;
 #define GR_LAUNCH_ATTN(DD, NCB_, NW_)                                                                                        \
   do {                                                                                                                       \
