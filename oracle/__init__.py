@@ -73,6 +73,34 @@ def attn_unified(q, k_shared, v_shared, cu_seqlens, k_unshared, v_unshared, u, s
     return out, lse
 
 
+def prefill_attn_causal(q, k, v, cu_seqlens, sm_scale, triples=None):
+    """Causal self-attention over packed prompts.  bf16 tensors are uint16 bit patterns.
+
+    q [total_L,Hq,d]; k, v [total_L,Hkv,d]; cu_seqlens int32 [B+1].
+    triples: int32 [n,3] rows (b, i, hq) to evaluate (i = token index inside request b), default all.
+    Returns (out fp64 [n,d], lse fp64 [n]).
+    """
+    lib = _load()
+    total_L, Hq, d = q.shape
+    Hkv = k.shape[1]
+    cu_seqlens = np.ascontiguousarray(cu_seqlens, dtype=np.int32)
+    B = len(cu_seqlens) - 1
+    if triples is None:
+        rows = [(b, i, h) for b in range(B) for i in range(int(cu_seqlens[b + 1] - cu_seqlens[b])) for h in range(Hq)]
+        triples = np.array(rows, dtype=np.int32).reshape(-1, 3)
+    triples = np.ascontiguousarray(triples, dtype=np.int32)
+    n = triples.shape[0]
+    out = np.empty((n, d), dtype=np.float64)
+    lse = np.empty(n, dtype=np.float64)
+    rc = lib.oracle_prefill_attn_causal(
+        ctypes.c_int(B), ctypes.c_int(Hq), ctypes.c_int(Hkv), ctypes.c_int(d), ctypes.c_float(float(sm_scale)),
+        _p(q, np.uint16), _p(k, np.uint16), _p(v, np.uint16), _p(cu_seqlens, np.int32), _p(triples, np.int32),
+        ctypes.c_int64(n), _p(out, np.float64), _p(lse, np.float64))
+    if rc != 0:
+        raise RuntimeError(f"oracle_prefill_attn_causal failed: {rc}")
+    return out, lse
+
+
 def check_table(items, V) -> int:
     items = np.ascontiguousarray(items, dtype=np.int32)
     return int(_load().oracle_check_table(_p(items, np.int32), ctypes.c_int64(items.shape[0]),

@@ -102,6 +102,57 @@ int oracle_attn_unified(int B, int W, int Hq, int Hkv, int d, int ND, int u, flo
 }
 
 /* ------------------------------------------------------------------------------------------------
+ * Causal self-attention over the prompt (the prefill phase that fills the shared cache: Section 2.2.1
+ * "Prefill", Section 5.1; the abstract's claim that prefill and decode go through one staged computation).
+ * The textbook definition, one query row at a time: token i of request b, query head hq (KV head hq / g),
+ *   s_j = sm_scale * <q_i, k_j>  for the keys j = 0..i of the same request (a token sees itself and what
+ *   precedes it), p = softmax(s), o = sum_j p_j v_j.
+ *
+ * q            bf16 bits [total_L, Hq, d]   (packed: request b owns rows cu_seqlens[b] .. cu_seqlens[b+1]-1)
+ * k, v         bf16 bits [total_L, Hkv, d]
+ * triples      int32 [n, 3] = (b, i, hq) rows to compute, i relative to the request
+ * out          fp64 [n, d];  lse_out fp64 [n] = log sum_{j<=i} exp(s_j), may be NULL
+ * ------------------------------------------------------------------------------------------------ */
+int oracle_prefill_attn_causal(int B, int Hq, int Hkv, int d, float sm_scale, const uint16_t *q, const uint16_t *k,
+                               const uint16_t *v, const int32_t *cu_seqlens, const int32_t *triples, int64_t n,
+                               double *out, double *lse_out) {
+    if (B <= 0 || Hq <= 0 || Hkv <= 0 || d <= 0 || Hq % Hkv != 0) return ORACLE_ERR_ARG;
+    const int g = Hq / Hkv;
+    int status = ORACLE_OK;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t t = 0; t < n; t++) {
+        const int b = triples[3 * t], i = triples[3 * t + 1], hq = triples[3 * t + 2];
+        if (b < 0 || b >= B || hq < 0 || hq >= Hq) { status = ORACLE_ERR_ARG; continue; }
+        const int64_t row0 = cu_seqlens[b];
+        const int64_t L = (int64_t)cu_seqlens[b + 1] - row0;
+        if (i < 0 || i >= L) { status = ORACLE_ERR_ARG; continue; }
+        const int hk = hq / g;
+        const int64_t n_keys = (int64_t)i + 1;
+        double *s = (double *)malloc(sizeof(double) * (size_t)n_keys);
+        if (!s) { status = ORACLE_ERR_MEM; continue; }
+        const uint16_t *qrow = q + ((row0 + i) * Hq + hq) * d;
+        double smax = -INFINITY;
+        for (int64_t j = 0; j < n_keys; j++) {
+            const uint16_t *krow = k + ((row0 + j) * Hkv + hk) * d;
+            double acc = 0.0;
+            for (int c = 0; c < d; c++) acc += (double)bf16_bits_to_float(qrow[c]) * (double)bf16_bits_to_float(krow[c]);
+            s[j] = (double)sm_scale * acc;
+            if (s[j] > smax) smax = s[j];
+        }
+        double denom = 0.0;
+        for (int64_t j = 0; j < n_keys; j++) { s[j] = exp(s[j] - smax); denom += s[j]; }
+        for (int c = 0; c < d; c++) {
+            double acc = 0.0;
+            for (int64_t j = 0; j < n_keys; j++) acc += s[j] * (double)bf16_bits_to_float(v[((row0 + j) * Hkv + hk) * d + c]);
+            out[t * d + c] = acc / denom;
+        }
+        if (lse_out) lse_out[t] = smax + log(denom);
+        free(s);
+    }
+    return status;
+}
+
+/* ------------------------------------------------------------------------------------------------
  * Item table helpers (Section 6.1: "pre-built valid item vocabulary").
  * The table is int32 [N, depth], rows sorted lexicographically and distinct.  A row is addressed by
  * its packed key  sum_c row[c] * V^(depth-1-c).

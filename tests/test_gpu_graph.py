@@ -91,3 +91,75 @@ def test_step_graph_replays_match_oracle_and_eager(oracle_lib):
         check_against_oracle(got, f"replay {rep}")
         for k in want:
             assert torch.equal(got[k], want[k]), f"replay {rep}: {k} differs from the eager step"
+
+
+def test_two_batches_on_two_streams_match_oracle(oracle_lib):
+    """Two independent batches, one stream each (equal priority), enqueued alternately so that their kernels
+    overlap on the GPU; each batch owns its inputs, outputs and workspaces.  Both must come out as the oracle says:
+    batch A runs the level-1 step (u = 2), batch B the level-2 step (u = 3) of the same request."""
+    import torch
+    import paper_2512_11529_amd as gr
+    gr.load_library()
+    cfg = gr_synth.get_config(1)
+    B, W, ND, Hq, Hkv, d, V = cfg.B, cfg.W, cfg.ND, cfg.Hq, cfg.Hkv, cfg.d, cfg.V
+    dev = torch.device("cuda:0")
+    items = gr_synth.make_item_table(cfg)
+    mask = gr.gr_item_mask_build(to_dev(items), V)
+    scale = float(np.float32(1 / np.sqrt(d)))
+    sc, pf, rg = gr_synth.initial_beam_state(B, W, ND)
+    logits = [gr_synth.make_logits(cfg, s) for s in range(ND)]
+    # beam states entering levels 1 and 2 (from the oracle: the batches' inputs do not depend on the code under test)
+    states = [dict(scores=sc, prefix=pf, range=rg)]
+    for s in range(2):
+        r = oracle_lib.beam_select(items, logits[s], states[s]["scores"], states[s]["prefix"], s)
+        states.append(dict(scores=r["scores"], prefix=r["prefix"], range=r["range"]))
+    torch.cuda.synchronize()
+
+    batches = []
+    for level in (1, 2):
+        a = gr_synth.make_attention_inputs(cfg, level)
+        cu = a["cu_seqlens"]
+        max_L, total_L = int(np.diff(cu).max()), int(cu[-1])
+        st = states[level]
+        bt = dict(level=level, a=a, u=level + 1, max_L=max_L, total_L=total_L, stream=torch.cuda.Stream(),
+                  q=bf16_to_dev(a["q"]), ks=bf16_to_dev(a["k_shared"]), vs=bf16_to_dev(a["v_shared"]), cu=to_dev(cu),
+                  ku0=bf16_to_dev(a["k_unshared"]), vu0=bf16_to_dev(a["v_unshared"]),
+                  logits=to_dev(logits[level]), sc=to_dev(st["scores"]), pf=to_dev(st["prefix"]), rg=to_dev(st["range"]),
+                  ws_attn=torch.empty(max(gr.attn_workspace_bytes(B, W, Hq, Hkv, d, max_L), 256), dtype=torch.uint8, device=dev),
+                  ws_sel=torch.empty(gr.select_workspace_bytes(B, W, V, ND), dtype=torch.uint8, device=dev))
+        bt["ku"], bt["vu"] = bt["ku0"].clone(), bt["vu0"].clone()
+        bt["out"] = torch.empty_like(bt["q"])
+        bt["sel"] = dict(parent=torch.empty((B, W), dtype=torch.int32, device=dev), token=torch.empty((B, W), dtype=torch.int32, device=dev),
+                         scores=torch.empty((B, W), dtype=torch.float32, device=dev), prefix=torch.empty((B, W, ND), dtype=torch.int32, device=dev),
+                         range=torch.empty((B, W, 2), dtype=torch.int32, device=dev), item_index=torch.empty((B, W), dtype=torch.int32, device=dev))
+        batches.append(bt)
+    torch.cuda.synchronize()
+
+    def enqueue(bt):
+        s = bt["stream"]
+        with torch.cuda.stream(s):
+            bt["ku"].copy_(bt["ku0"]); bt["vu"].copy_(bt["vu0"])
+        gr.gr_beam_attn(bt["q"], bt["ks"], bt["vs"], bt["cu"], bt["ku"], bt["vu"], bt["u"], scale, bt["max_L"], bt["total_L"],
+                        out=bt["out"], workspace=bt["ws_attn"], stream=s)
+        gr.gr_beam_select(mask, bt["logits"], bt["sc"], bt["pf"], bt["rg"], bt["level"], out=bt["sel"], workspace=bt["ws_sel"], stream=s)
+        gr.gr_beam_reorder(bt["sel"]["parent"], bt["ku"], bt["vu"], bt["u"], stream=s)
+
+    for _ in range(8):                     # alternate, no synchronisation in between: the two streams run concurrently
+        for bt in batches:
+            enqueue(bt)
+    torch.cuda.synchronize()
+
+    for bt in batches:
+        a, level, u = bt["a"], bt["level"], bt["u"]
+        ref_out, _ = oracle_lib.attn_unified(a["q"], a["k_shared"], a["v_shared"], a["cu_seqlens"], a["k_unshared"], a["v_unshared"], u, scale)
+        err = np.abs(bt["out"].float().cpu().numpy() - ref_out.reshape(B, W, Hq, d)).max()
+        assert err <= 2e-2, f"level {level}: attention max-abs {err}"
+        st = states[level]
+        ref = oracle_lib.beam_select(items, logits[level], st["scores"], st["prefix"], level)
+        for k in ("parent", "token", "prefix", "range", "item_index"):
+            np.testing.assert_array_equal(bt["sel"][k].cpu().numpy(), ref[k], err_msg=f"level {level}: {k}")
+        np.testing.assert_allclose(bt["sel"]["scores"].cpu().numpy(), ref["scores"], rtol=1e-5, atol=0)
+        for name, src in (("ku", a["k_unshared"]), ("vu", a["v_unshared"])):
+            want = oracle_lib.unshared_reorder(src.copy(), ref["parent"])
+            bits = bt[name].view(torch.int16).cpu().numpy().view(np.uint16)
+            np.testing.assert_array_equal(bits[:, :, :u], want[:, :, :u], err_msg=f"level {level}: reordered {name}")
