@@ -85,6 +85,36 @@ size_t gr_beam_attn_workspace_bytes(const gr_attn_params* p);
 gr_status gr_beam_attn(const gr_attn_params* p, void* workspace, size_t workspace_bytes, void* stream);
 
 /* ------------------------------------------------------------------------------------------------
+ * gr_prefill_attn - causal self-attention over the packed prompts: the prefill phase that produces the
+ * shared cache (Section 2.2.1 "Prefill"; Section 5.1: the shared cache stores the prompt's token-level
+ * outputs of the prefill phase; the abstract's single staged computation for prefill and decode).
+ *
+ * For request b, token i (0 <= i < L_b), query head hq with KV head hq / (Hq/Hkv):
+ *     out[i, hq, :] = softmax_j( sm_scale * <q[i, hq], k[j, kvh]> ) . v[j, kvh]   over the keys j = 0..i
+ * of the same request.  It runs through the tiles of gr_beam_attn (bf16 MFMA, fp32 accumulation, bf16
+ * output): a block of query rows walks the request's K/V tiles up to its own last token and masks
+ * the tiles on the diagonal.  No workspace.  Only enqueues on `stream`; no synchronisation.
+ *
+ * Supported: d in {64, 128}; Hq % Hkv == 0; total_L < 2^31; max_L * Hq/Hkv < 2^22;
+ * max_L * Hkv * d * 2 < 2^32; max_L * Hq * d < 2^31.
+ * ------------------------------------------------------------------------------------------------ */
+typedef struct {
+  int32_t B, Hq, Hkv, d;
+  int32_t max_L;              /* host copy of max_b L_b (sizes the grid)                             */
+  int64_t total_L;            /* host copy of cu_seqlens[B]                                          */
+  float   sm_scale;           /* multiplies the scores; must be positive and finite                  */
+  const void*    q;           /* bf16 [total_L, Hq, d]  (device), packed like k and v                */
+  const void*    k;           /* bf16 [total_L, Hkv, d]                                              */
+  const void*    v;           /* bf16 [total_L, Hkv, d]                                              */
+  const int32_t* cu_seqlens;  /* int32 [B+1] (device): request b owns rows cu[b] .. cu[b+1]-1        */
+  void*          out;         /* bf16 [total_L, Hq, d]                                               */
+  float*         lse_out;     /* fp32 [total_L, Hq] natural-log sum-exp of the scaled scores; or NULL */
+} gr_prefill_params;
+
+/* Errors: INVALID_ARG, UNSUPPORTED, HIP.  An empty batch (total_L == 0) is GR_OK and launches nothing. */
+gr_status gr_prefill_attn(const gr_prefill_params* p, void* stream);
+
+/* ------------------------------------------------------------------------------------------------
  * gr_item_mask_build - valid-item mask, built once at load time (Section 6.1: dense masks are
  * pre-generated during model loading; the last level is kept in sparse form).
  *

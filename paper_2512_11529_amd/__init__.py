@@ -16,7 +16,7 @@ import os
 
 from . import build as _build
 
-__all__ = ["load_library", "gr_beam_attn", "gr_item_mask_build", "gr_beam_select", "gr_beam_select_noalloc", "gr_beam_reorder",
+__all__ = ["load_library", "gr_beam_attn", "gr_prefill_attn", "gr_item_mask_build", "gr_beam_select", "gr_beam_select_noalloc", "gr_beam_reorder",
            "gr_status_string",
            "attn_workspace_bytes", "select_workspace_bytes", "GrError", "GR_SELECT_FORCE_DENSE", "LIB_PATH",
            "gr_diag_stream_read", "gr_diag_mfma_loop", "gr_diag_attn_plan"]
@@ -38,6 +38,13 @@ class _AttnParams(ctypes.Structure):
                 ("total_L", ctypes.c_int64), ("sm_scale", ctypes.c_float),
                 ("q", ctypes.c_void_p), ("k_shared", ctypes.c_void_p), ("v_shared", ctypes.c_void_p),
                 ("cu_seqlens", ctypes.c_void_p), ("k_unshared", ctypes.c_void_p), ("v_unshared", ctypes.c_void_p),
+                ("out", ctypes.c_void_p), ("lse_out", ctypes.c_void_p)]
+
+
+class _PrefillParams(ctypes.Structure):
+    _fields_ = [("B", ctypes.c_int32), ("Hq", ctypes.c_int32), ("Hkv", ctypes.c_int32), ("d", ctypes.c_int32),
+                ("max_L", ctypes.c_int32), ("total_L", ctypes.c_int64), ("sm_scale", ctypes.c_float),
+                ("q", ctypes.c_void_p), ("k", ctypes.c_void_p), ("v", ctypes.c_void_p), ("cu_seqlens", ctypes.c_void_p),
                 ("out", ctypes.c_void_p), ("lse_out", ctypes.c_void_p)]
 
 
@@ -84,6 +91,8 @@ def load_library(path: str = None):
     lib.gr_diag_stream_read.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_void_p]
     lib.gr_diag_mfma_loop.restype = ctypes.c_int32
     lib.gr_diag_mfma_loop.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p]
+    lib.gr_prefill_attn.restype = ctypes.c_int32
+    lib.gr_prefill_attn.argtypes = [ctypes.POINTER(_PrefillParams), ctypes.c_void_p]
     lib.gr_diag_attn_plan.restype = ctypes.c_int32
     lib.gr_diag_attn_plan.argtypes = [ctypes.c_int32, ctypes.c_int32]
     lib.gr_diag_mfma_flops.restype = ctypes.c_double
@@ -169,6 +178,33 @@ def gr_beam_attn(q, k_shared, v_shared, cu_seqlens, k_unshared, v_unshared, u, s
     rc = lib.gr_beam_attn(ctypes.byref(p), _ptr(workspace), ws_bytes, _stream(stream))
     if rc != 0:
         raise GrError(rc, "gr_beam_attn")
+    return out, lse_out
+
+
+def gr_prefill_attn(q, k, v, cu_seqlens, sm_scale, max_L, total_L, out=None, lse_out=None, stream=None):
+    """Causal self-attention over packed prompts.  bf16 CUDA tensors: q [total_L,Hq,d], k/v [total_L,Hkv,d];
+    cu_seqlens int32 [B+1].  max_L / total_L are host integers.  Returns (out bf16 [total_L,Hq,d], lse or None)."""
+    import torch
+    lib = load_library()
+    T, Hq, d = q.shape
+    Hkv = k.shape[1]
+    B = cu_seqlens.shape[0] - 1
+    _check(q, torch.bfloat16, None, "q")
+    _check(k, torch.bfloat16, (T, Hkv, d), "k")
+    _check(v, torch.bfloat16, (T, Hkv, d), "v")
+    _check(cu_seqlens, torch.int32, (B + 1,), "cu_seqlens")
+    if T < int(total_L):
+        raise ValueError("q has fewer rows than total_L")
+    if out is None:
+        out = torch.empty_like(q)
+    _check(out, torch.bfloat16, tuple(q.shape), "out")
+    if lse_out is not None:
+        _check(lse_out, torch.float32, (T, Hq), "lse_out")
+    p = _PrefillParams(B, Hq, Hkv, d, int(max_L), int(total_L), float(sm_scale), q.data_ptr(), k.data_ptr(), v.data_ptr(),
+                       cu_seqlens.data_ptr(), out.data_ptr(), lse_out.data_ptr() if lse_out is not None else None)
+    rc = lib.gr_prefill_attn(ctypes.byref(p), _stream(stream))
+    if rc != 0:
+        raise GrError(rc, "gr_prefill_attn")
     return out, lse_out
 
 

@@ -265,7 +265,12 @@ struct AttnTile {
   }
 };
 
-template <int D, int NCB, int NWAVES>
+// CAUSAL = false: the decode step described above.  CAUSAL = true: causal self-attention over the packed prompts
+// (the prefill that fills the shared cache, Sections 2.2.1 / 5.1) through the same tiles: request b's query rows are
+// its own tokens (row r = token r / g, head r % g of the KV group), a row block only walks the K/V tiles up to its
+// last token, scores of keys after a row's token are set to -inf on the tiles that straddle the diagonal, and there
+// is no own-token stage and no L split.
+template <int D, int NCB, int NWAVES, bool CAUSAL>
 __global__ void __launch_bounds__(NWAVES * 64) __attribute__((amdgpu_waves_per_eu(NCB == 1 ? 2 : 1, NCB == 1 ? 2 : 1)))
 k_beam_attn(AttnCtx c) {
   using T = AttnTile<D, NCB>;
@@ -290,7 +295,8 @@ k_beam_attn(AttnCtx c) {
   const int xcd = (int)(id & 7u);
   const unsigned slot = id >> 3;
   const int group = (int)(slot / (unsigned)c.MB) * 8 + xcd;
-  const int mbi = (int)(slot % (unsigned)c.MB);
+  int mbi = (int)(slot % (unsigned)c.MB);
+  if (CAUSAL) mbi = c.MB - 1 - mbi;            // the blocks with the most keys to visit start first
   if (group >= c.n_groups) return;
   const unsigned gq = (unsigned)group / (unsigned)c.nsplit;
   const int sp = (int)((unsigned)group - gq * (unsigned)c.nsplit);
@@ -300,9 +306,12 @@ k_beam_attn(AttnCtx c) {
 
   const int row0 = c.cu[b];
   const int Lb = c.cu[b + 1] - row0;
+  const int Mb = CAUSAL ? Lb * c.g : c.M;                      // query rows of this (request, KV head)
+  if (CAUSAL && mbi * (NWAVES * 32 * NCB) >= Mb) return;       // (before any barrier: the whole workgroup leaves)
   int chunk = (int)(((unsigned)Lb + (unsigned)c.nsplit - 1u) / (unsigned)c.nsplit);
   chunk = ((chunk + KT - 1) / KT) * KT;
-  const int seg0 = min(Lb, sp * chunk), seg1 = min(Lb, seg0 + chunk);
+  const int seg0 = CAUSAL ? 0 : min(Lb, sp * chunk);
+  const int seg1 = CAUSAL ? (min((mbi + 1) * (NWAVES * 32 * NCB), Mb) - 1) / c.g + 1 : min(Lb, seg0 + chunk);
   const int ntiles = (seg1 - seg0 + KT - 1) / KT;
 
   // ---- Q: the workgroup's MWG query rows are fetched with coalesced 16-byte pieces (a row = PPR
@@ -312,7 +321,8 @@ k_beam_attn(AttnCtx c) {
   static_assert(NCB == 1, "one column block per wave");
   constexpr int QP = MWG * PPR / NT;             // 16-byte pieces of Q per thread
   const float rcp_g = 1.0f / (float)c.g;
-  const uint16_t* q_b = c.q + (size_t)b * c.W * c.Hq * D;      // this request's queries; offsets inside it fit 32 bits
+  // this request's queries (decode: its W beams; prefill: its own tokens); offsets inside it fit 32 bits
+  const uint16_t* q_b = c.q + (CAUSAL ? (size_t)row0 : (size_t)b * c.W) * c.Hq * D;
   uint4 qpiece[QP];
 #pragma unroll
   for (int i = 0; i < QP; i++) {
@@ -321,13 +331,17 @@ k_beam_attn(AttnCtx c) {
     int w, j;
     divmod_small(r, c.g, rcp_g, &w, &j);
     qpiece[i] = make_uint4(0, 0, 0, 0);
-    if (r < c.M) qpiece[i] = *(const uint4*)(q_b + (uint32_t)((w * c.Hq + kvh * c.g + j) * D + col));
+    if (r < Mb) qpiece[i] = *(const uint4*)(q_b + (uint32_t)((w * c.Hq + kvh * c.g + j) * D + col));
   }
   int qrow[NCB];       // local query row or -1
   {
     const int r = mbi * MWG + wave * 32 + n32;
-    qrow[0] = (r < c.M) ? r : -1;
+    qrow[0] = (r < Mb) ? r : -1;
   }
+  // causal mode: the last key a column may see, and the first token of the wave's 32 columns (tiles that end at or
+  // before it need no masking).  Columns past the end of the request keep everything (their output is dropped).
+  const int tokq = (CAUSAL && qrow[0] >= 0) ? qrow[0] / c.g : 0x7fffffff;
+  const int wave_tok0 = CAUSAL ? (mbi * MWG + wave * 32 * NCB) / c.g : 0x7fffffff;
 
   f32x16 o_acc[D / 32][NCB];
 #pragma unroll
@@ -383,11 +397,11 @@ k_beam_attn(AttnCtx c) {
   static_assert(NCB == 1, "one column block per wave");
   constexpr int UR = 32;                                 // rows of a mini-tile
   constexpr int UP = UR * PPR / 64;                      // 16-byte pieces per lane and tensor
-  const bool own_stage = sp == 0 && c.u > 0;
+  const bool own_stage = !CAUSAL && sp == 0 && c.u > 0;
   auto wave_rows = [&](int wv, int* first_beam) {        // rows of wave wv's mini-tiles, and its first beam
     const int r_first = mbi * MWG + wv * 32;
-    if (r_first >= c.M) { *first_beam = 0; return 0; }
-    const int r_last = min(r_first + 31, c.M - 1);
+    if (r_first >= Mb) { *first_beam = 0; return 0; }
+    const int r_last = min(r_first + 31, Mb - 1);
     *first_beam = r_first / c.g;
     return (r_last / c.g - *first_beam + 1) * c.u;
   };
@@ -467,7 +481,20 @@ k_beam_attn(AttnCtx c) {
     // go to s_out.  The reference maximum is settled first (raising it, and rescaling O and the running sum, is a
     // rare wave-uniform branch), so that the tile's MFMAs and exponentials form one straight-line block.
     float mx_cur = -INFINITY;
+    auto causal_mask = [&](f32x16 (&s)[KT / 32][NCB], int tok0) {
+#pragma unroll
+      for (int sub = 0; sub < KT / 32; sub++)
+#pragma unroll
+        for (int i = 0; i < 16; i++) {
+          const int kv = tok0 + sub * 32 + 8 * (i / 4) + 4 * G + (i % 4);
+          s[sub][0][i] = (kv > tokq) ? -INFINITY : s[sub][0][i];
+        }
+    };
     auto step = [&](f32x16 (&s_in)[KT / 32][NCB], f32x16 (&s_out)[KT / 32][NCB], int t) {
+      if (CAUSAL && seg0 + t * KT + KT - 1 > wave_tok0) {         // (wave-uniform) this tile reaches past the wave's first token
+        causal_mask(s_in, seg0 + t * KT);
+        mx_cur = T::colmax(s_in);
+      }
       if (__any(mx_cur * c.c > m_run[0] * c.c + T::kLazy)) {
         const float m_new = fmaxf(m_run[0], mx_cur);
         const float alpha = __builtin_amdgcn_exp2f((m_run[0] - m_new) * c.c);
@@ -500,6 +527,7 @@ k_beam_attn(AttnCtx c) {
             for (int cb = 0; cb < NCB; cb++) s_in[sub][cb][i] = (kv >= seg1) ? -INFINITY : s_in[sub][cb][i];
           }
       }
+      if (CAUSAL) causal_mask(s_in, tok0);
       bf16x8 pop[KT / 16][NCB];
       float alpha[NCB];
       bool upd[NCB];
@@ -635,7 +663,7 @@ k_beam_attn(AttnCtx c) {
           *(uint2*)(&s_o[n32 * KSTR + db * 32 + 8 * q4 + 4 * G]) = st;
         }
       const float rcp_g2 = 1.0f / (float)c.g;
-      uint16_t* out_b = c.out + (size_t)b * c.W * c.Hq * D;
+      uint16_t* out_b = c.out + (CAUSAL ? (size_t)row0 : (size_t)b * c.W) * c.Hq * D;
 #pragma unroll
       for (int i = 0; i < 32 * PPR / 64; i++) {
         const int p = lane + 64 * i, rl = p / PPR, col = (p % PPR) * 8;
@@ -643,12 +671,12 @@ k_beam_attn(AttnCtx c) {
         int w, j;
         divmod_small(rr, c.g, rcp_g2, &w, &j);
         const uint4 v = *(const uint4*)(&s_o[rl * KSTR + col]);
-        if (rr < c.M) *(uint4*)(out_b + (uint32_t)((w * c.Hq + kvh * c.g + j) * D + col)) = v;
+        if (rr < Mb) *(uint4*)(out_b + (uint32_t)((w * c.Hq + kvh * c.g + j) * D + col)) = v;
       }
       if (c.lse && G == 0 && r >= 0) {
         int w, j;
         divmod_small(r, c.g, rcp_g2, &w, &j);
-        c.lse[((size_t)b * c.W + w) * c.Hq + kvh * c.g + j] = (l_tot > 0.f) ? (m * c.c + __builtin_amdgcn_logf(l_tot)) * kLn2 : -INFINITY;
+        c.lse[((CAUSAL ? (size_t)row0 : (size_t)b * c.W) + w) * c.Hq + kvh * c.g + j] = (l_tot > 0.f) ? (m * c.c + __builtin_amdgcn_logf(l_tot)) * kLn2 : -INFINITY;
       }
     } else {
       // this segment's unnormalised fp32 partial O and (max, sum): staged through LDS like the final
@@ -676,7 +704,7 @@ k_beam_attn(AttnCtx c) {
           int w, j;
           divmod_small(rr, c.g, rcp_g2, &w, &j);
           const f32x4 v = *(const f32x4*)(&s_p[rl * PSTR + col]);
-          if (rr < c.M) *(f32x4*)(part_b + (size_t)(w * c.Hq + kvh * c.g + j) * D + h * CW + col) = v;
+          if (rr < Mb) *(f32x4*)(part_b + (size_t)(w * c.Hq + kvh * c.g + j) * D + h * CW + col) = v;
         }
       }
       if (G == 0 && r >= 0) {
@@ -850,8 +878,8 @@ extern "C" gr_status gr_beam_attn(const gr_attn_params* p, void* workspace, size
   const size_t lds = lds_tiles > lds_own ? lds_tiles : lds_own;
 #define GR_LAUNCH_ATTN(DD, NCB_, NW_)                                                                                        \
   do {                                                                                                                       \
-    GR_HIP_TRY(hipFuncSetAttribute((const void*)k_beam_attn<DD, NCB_, NW_>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)); \
-    hipLaunchKernelGGL((k_beam_attn<DD, NCB_, NW_>), dim3((unsigned)grid), dim3(NW_ * 64), lds, stream, c);                  \
+    GR_HIP_TRY(hipFuncSetAttribute((const void*)k_beam_attn<DD, NCB_, NW_, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)); \
+    hipLaunchKernelGGL((k_beam_attn<DD, NCB_, NW_, false>), dim3((unsigned)grid), dim3(NW_ * 64), lds, stream, c);           \
   } while (0)
   if (p->d == 128) {
     if (plan.mwg == 256) GR_LAUNCH_ATTN(128, 1, 8); else GR_LAUNCH_ATTN(128, 1, 4);
@@ -865,6 +893,56 @@ extern "C" gr_status gr_beam_attn(const gr_attn_params* p, void* workspace, size
     if (p->d == 128) hipLaunchKernelGGL((k_attn_merge<128>), dim3(mgrid), dim3(256), 0, stream, c);
     else hipLaunchKernelGGL((k_attn_merge<64>), dim3(mgrid), dim3(256), 0, stream, c);
   }
+  GR_HIP_TRY(hipGetLastError());
+  return GR_OK;
+}
+
+// Causal prompt attention through the same kernel (CAUSAL = true).
+extern "C" gr_status gr_prefill_attn(const gr_prefill_params* p, void* stream_) {
+  hipStream_t stream = (hipStream_t)stream_;
+  if (!p) return GR_ERR_INVALID_ARG;
+  if (p->B <= 0 || p->Hq <= 0 || p->Hkv <= 0 || p->d <= 0 || p->Hq % p->Hkv) return GR_ERR_INVALID_ARG;
+  if (p->max_L < 0 || p->total_L < 0 || p->total_L > (int64_t)p->max_L * p->B) return GR_ERR_INVALID_ARG;
+  if (!p->cu_seqlens) return GR_ERR_INVALID_ARG;
+  if (p->total_L > 0 && (!p->q || !p->k || !p->v || !p->out)) return GR_ERR_INVALID_ARG;
+  if (!(p->sm_scale > 0.f) || !(p->sm_scale < INFINITY)) return GR_ERR_INVALID_ARG;
+  if (p->d != 64 && p->d != 128) return GR_ERR_UNSUPPORTED;
+  if (p->total_L >= ((int64_t)1 << 31)) return GR_ERR_UNSUPPORTED;
+  if ((int64_t)p->max_L * p->Hkv * p->d * 2 >= ((int64_t)1 << 32)) return GR_ERR_UNSUPPORTED;   // one request's K (or V) must fit a buffer descriptor
+  const int g = p->Hq / p->Hkv;
+  if ((int64_t)p->max_L * g >= ((int64_t)1 << 22)) return GR_ERR_UNSUPPORTED;                   // row indices go through divmod_small
+  if ((int64_t)p->max_L * p->Hq * p->d >= ((int64_t)1 << 31)) return GR_ERR_UNSUPPORTED;        // offsets inside one request fit 32 bits
+  if (p->total_L == 0 || p->max_L == 0) return GR_OK;
+
+  AttnCtx c;
+  c.B = p->B; c.W = 0; c.Hq = p->Hq; c.Hkv = p->Hkv; c.g = g; c.ND = 0; c.u = 0;
+  c.M = p->max_L * g;                                        // the longest request's rows size the grid
+  const int mwg = c.M <= 128 ? 128 : 256;
+  c.MB = (c.M + mwg - 1) / mwg;
+  c.nsplit = 1;
+  c.n_groups = p->B * p->Hkv;
+  c.c = p->sm_scale * kLog2e;
+  c.q = (const uint16_t*)p->q; c.ks = (const uint16_t*)p->k; c.vs = (const uint16_t*)p->v;
+  c.cu = p->cu_seqlens; c.ku = nullptr; c.vu = nullptr;
+  c.out = (uint16_t*)p->out; c.lse = p->lse_out;
+  c.part_o = nullptr; c.part_ml = nullptr; c.order = nullptr;
+  const int64_t groups_padded = ((int64_t)c.n_groups + 7) / 8 * 8;
+  const int64_t grid = groups_padded * c.MB;
+  if (grid >= ((int64_t)1 << 31)) return GR_ERR_UNSUPPORTED;
+  const size_t lds_tiles = (size_t)2 * KT * ((p->d + 8) + (p->d + 32)) * 2;
+  const size_t lds_out = (size_t)mwg * (p->d + 8) * 2;        // Q staging and the output staging of the epilogue
+  const size_t lds = lds_tiles > lds_out ? lds_tiles : lds_out;
+#define GR_LAUNCH_PREFILL(DD, NW_)                                                                                              \
+  do {                                                                                                                         \
+    GR_HIP_TRY(hipFuncSetAttribute((const void*)k_beam_attn<DD, 1, NW_, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)); \
+    hipLaunchKernelGGL((k_beam_attn<DD, 1, NW_, true>), dim3((unsigned)grid), dim3(NW_ * 64), lds, stream, c);                 \
+  } while (0)
+  if (p->d == 128) {
+    if (mwg == 256) GR_LAUNCH_PREFILL(128, 8); else GR_LAUNCH_PREFILL(128, 4);
+  } else {
+    if (mwg == 256) GR_LAUNCH_PREFILL(64, 8); else GR_LAUNCH_PREFILL(64, 4);
+  }
+#undef GR_LAUNCH_PREFILL
   GR_HIP_TRY(hipGetLastError());
   return GR_OK;
 }
