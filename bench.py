@@ -269,7 +269,7 @@ def main():
             sel_by_level[f"level{s}"] = dict(ms=round(float(np.mean(ms)), 4), live_rows=live_rows[s])
 
     # ---------------- extras, outside the headline's timed region
-    roofline_select, reorder, graph, streams, peaks = None, None, None, None, None
+    roofline_select, reorder, graph, streams, peaks, prefill = None, None, None, None, None, None
     if not args.no_extras:
         # (0) the item step on its dense paths: every live row streamed in full (GR_SELECT_FORCE_DENSE, and mask = NULL),
         # on the levels where all B*W rows are live.  Algorithmic bytes = live rows x (4V logits + V/8 mask bits); the time
@@ -361,7 +361,21 @@ def main():
             del buf2
         except Exception as e:
             streams = dict(error=f"{type(e).__name__}: {e}"[:300])
-        # (4) what the machine sustains, next to the datasheet peaks
+        # (4) the prefill that would have produced the shared cache: causal attention over the same packed prompts
+        try:
+            qp = torch.randn((total_L, Hq, d), device=dev).to(torch.bfloat16)
+            op = torch.empty_like(qp)
+            run_p = lambda: gr.gr_prefill_attn(qp, k_sh, v_sh, d_cu, scale, max_L, total_L, out=op)
+            for _ in range(3):
+                run_p()
+            ms = _elapsed(torch, run_p, 5)
+            pf_flops = 4.0 * Hq * d * float((lens * (lens + 1) // 2).sum())
+            prefill = dict(ms=round(ms, 4), TFLOPs=round(pf_flops / (ms * 1e-3) / 1e12, 1), frac=round(pf_flops / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
+                           flops=pf_flops, note="causal: 4*Hq*d*sum_b L_b(L_b+1)/2 flops; q is N(0,1) bf16 [total_L,Hq,d]")
+            del qp, op
+        except Exception as e:
+            prefill = dict(error=f"{type(e).__name__}: {e}"[:300])
+        # (5) what the machine sustains, next to the datasheet peaks
         try:
             peaks = measured_peaks(torch, gr, dev)
             roofline["peak_measured"] = peaks["bf16_mfma_TFLOPs"]
@@ -406,7 +420,7 @@ def main():
         roofline=roofline, roofline_select=roofline_select, cpu_baseline=cpu,
         attn=dict(ms_by_u={f"u{s + 1}": round(float(np.mean([attn_ms[i] for i in range(K) if i % ND == s] or [0])), 4) for s in range(ND)},
                   tflops=round(attn_tflops, 2), ms_first20_after_idle=round(cold_ms, 4)),
-        select=sel_by_level, reorder=reorder, graph=graph, two_streams=streams, peaks_measured=peaks,
+        select=sel_by_level, reorder=reorder, graph=graph, two_streams=streams, prefill=prefill, peaks_measured=peaks,
         prewarm=dict(ms=args.prewarm_ms, steps=prewarm_steps), wall_s=round(wall, 3), input_gen_s=round(t_gen, 1))
     print(json.dumps(line))
 

@@ -9,7 +9,7 @@ CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libgr.so")
 SOURCES = ["gr_api.hip", "gr_mask.hip", "gr_select.hip", "gr_attn.hip", "gr_reorder.hip", "gr_diag.hip"]
 # packed-fp32 VALU forms are disabled on purpose (hipcc would otherwise form them from scalar code)
-COMMON = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang",
+COMMON = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-Wno-inline-asm", "-Xclang", "-target-feature", "-Xclang",
           "-packed-fp32-ops", "-Wno-unused-command-line-argument", "-I", os.path.join(ROOT, "include"), "-I", CSRC]
 PER_FILE = {"gr_select.hip": ["-ffp-contract=off"]}
 

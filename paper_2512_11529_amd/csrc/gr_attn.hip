@@ -65,15 +65,37 @@ __device__ __forceinline__ void divmod_small(int n, int d, float rcp_d, int* q, 
 // = 2 sub-tiles x NCB column blocks of 32x32 fp32 accumulators.
 template <int D, int NCB>
 struct AttnTile {
-  static constexpr int KSTR = D + 8;     // K rows: +16 B  -> ds_read_b128 of 32 consecutive rows is conflict-free
+  // Prompt tiles arrive by direct global->LDS loads: a wave-level load writes 1 KiB of consecutive LDS (lane l -> bytes
+  // 16 l ..), so tile rows cannot be padded.  Instead the 16-byte pieces of a row are stored permuted (piece p of row r
+  // sits in slot p ^ swz(r); the lane that fills slot s fetches piece s ^ swz(r) from memory), chosen so that the
+  // operand reads below hit every bank group once:
+  //   K (ds_read_b128, 16 lanes = 16 consecutive rows, same piece): swz = r & 15 (256-byte rows) or (r >> 1) & 7 (128-byte rows);
+  //   V (ds_read_b64_tr_b16, 32 lanes = 4 consecutive rows x 4 pieces):  swz = 4 (r & 3)  or  4 ((r >> 1) & 1).
+  static constexpr int PPRW = D / 8;                                       // 16-byte pieces per row
+  static __device__ __forceinline__ int swz_k(int r) { return D == 128 ? (r & 15) : ((r >> 1) & 7); }
+  static __device__ __forceinline__ int swz_v(int r) { return D == 128 ? 4 * (r & 3) : 4 * ((r >> 1) & 1); }
+  // per-lane element offsets of the operand reads inside a tile (fixed for the whole kernel)
+  struct Rd { int k[D / 16]; int v[D / 32]; };
+  static __device__ __forceinline__ Rd make_rd(int lane) {
+    const int G = lane >> 5, n32 = lane & 31;
+    Rd r;
+#pragma unroll
+    for (int ks = 0; ks < D / 16; ks++) r.k[ks] = n32 * D + ((2 * ks + G) ^ swz_k(n32)) * 8;
+    const int vrow = 4 * G + ((lane & 15) >> 2);
+#pragma unroll
+    for (int db = 0; db < D / 32; db++)
+      r.v[db] = vrow * D + ((4 * db + 2 * ((lane >> 4) & 1) + ((lane & 3) >> 1)) ^ swz_v(vrow)) * 8 + 4 * (lane & 1);
+    return r;
+  }
+  static constexpr int KSTR = D + 8;     // padded rows of the Q / output staging and of the own-token mini-tiles (+16 B)
   // V rows: +64 B.  One ds_read_b64_tr_b16 serves 32 lanes per cycle = 4 rows x 2 column halves x 32 bytes; a row
   // stride of 64 B modulo 256 B puts those eight 32-byte groups on eight different bank groups (with +32 B the
   // second half of row r and the first half of row r+1 share banks: a 2-way conflict on every V operand read).
-  static constexpr int VSTR = D + 32;
+  static constexpr int VSTR = D + 32;    // (own-token mini-tiles only; prompt V tiles are unpadded and swizzled)
 
   // S^T = K . Q^T from the K tile in LDS (A operand) and Q in registers (B operand)
   static __device__ __forceinline__ void qk(const uint16_t* sk, const bf16x8 (&qop)[NCB][D / 16], f32x16 (&s)[KT / 32][NCB],
-                                            int n32, int G) {
+                                            const Rd& rdo) {
 #pragma unroll
     for (int sub = 0; sub < KT / 32; sub++)
 #pragma unroll
@@ -84,10 +106,10 @@ struct AttnTile {
     constexpr int N = (KT / 32) * (D / 16), PF = 4;
     bf16x8 a[N];
 #pragma unroll
-    for (int i = 0; i < PF; i++) a[i] = as_bf16x8(*(const uint4*)(&sk[((i % 2) * 32 + n32) * KSTR + (i / 2) * 16 + G * 8]));
+    for (int i = 0; i < PF; i++) a[i] = as_bf16x8(*(const uint4*)(&sk[(i % 2) * 32 * D + rdo.k[i / 2]]));
 #pragma unroll
     for (int i = 0; i < N; i++) {
-      if (i + PF < N) a[i + PF] = as_bf16x8(*(const uint4*)(&sk[(((i + PF) % 2) * 32 + n32) * KSTR + ((i + PF) / 2) * 16 + G * 8]));
+      if (i + PF < N) a[i + PF] = as_bf16x8(*(const uint4*)(&sk[((i + PF) % 2) * 32 * D + rdo.k[(i + PF) / 2]]));
 #pragma unroll
       for (int cb = 0; cb < NCB; cb++) s[i % 2][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], qop[cb][i / 2], s[i % 2][cb], 0, 0, 0);
     }
@@ -101,15 +123,13 @@ struct AttnTile {
   }
 
   // O^T += V^T . P^T.  V^T operand: d = 32*db + (lane%32), k slot e <-> token 16*s + 8*(e/4) + 4*G + e%4
-  static __device__ __forceinline__ void pv(const uint16_t* sv, const bf16x8 (&pop)[KT / 16][NCB], f32x16 (&o)[D / 32][NCB], int lane) {
-    const int G = lane >> 5;
+  static __device__ __forceinline__ void pv(const uint16_t* sv, const bf16x8 (&pop)[KT / 16][NCB], f32x16 (&o)[D / 32][NCB], const Rd& rdo) {
     typedef short s16x8 __attribute__((ext_vector_type(8)));
     constexpr int N = (KT / 16) * (D / 32), PF = 4;      // operand i: slab i / (D/32), d block i % (D/32)
-    const uint16_t* base = sv + (4 * G + ((lane & 15) >> 2)) * VSTR + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
     auto rd = [&](int i) {
-      const uint16_t* p0 = base + (i / (D / 32)) * 16 * VSTR + (i % (D / 32)) * 32;
+      const uint16_t* p0 = sv + (i / (D / 32)) * 16 * D + rdo.v[i % (D / 32)];
       s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p0));
-      s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p0 + 8 * VSTR));
+      s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p0 + 8 * D));
       s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
       return __builtin_bit_cast(bf16x8, both);
     };
@@ -156,17 +176,14 @@ struct AttnTile {
   }
   static __device__ __forceinline__ void fused(const uint16_t* sk_next, const uint16_t* sv_cur, const bf16x8 (&qop)[NCB][D / 16],
                                                const f32x16 (&s_cur)[KT / 32][NCB], f32x16 (&s_next)[KT / 32][NCB],
-                                               f32x16 (&o)[D / 32][NCB], float mc, float c, float& l_run, float& mx_next, int lane) {
+                                               f32x16 (&o)[D / 32][NCB], float mc, float c, float& l_run, float& mx_next, const Rd& rdo) {
     static_assert(NCB == 1, "one column block per wave");
     typedef short s16x8 __attribute__((ext_vector_type(8)));
-    const int G = lane >> 5, n32 = lane & 31;
-    const uint16_t* kb = sk_next + n32 * KSTR + G * 8;
-    const uint16_t* vb = sv_cur + (4 * G + ((lane & 15) >> 2)) * VSTR + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
-    auto rdk = [&](int i) { return as_bf16x8(*(const uint4*)(kb + (i % 2) * 32 * KSTR + (i / 2) * 16)); };
+    auto rdk = [&](int i) { return as_bf16x8(*(const uint4*)(sk_next + (i % 2) * 32 * D + rdo.k[i / 2])); };
     auto rdv = [&](int i) {
-      const uint16_t* p0 = vb + (i / (D / 32)) * 16 * VSTR + (i % (D / 32)) * 32;
+      const uint16_t* p0 = sv_cur + (i / (D / 32)) * 16 * D + rdo.v[i % (D / 32)];
       s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p0));
-      s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p0 + 8 * VSTR));
+      s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p0 + 8 * D));
       s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
       return __builtin_bit_cast(bf16x8, both);
     };
@@ -277,14 +294,19 @@ k_beam_attn(AttnCtx c) {
   constexpr int NT = NWAVES * 64;
   constexpr int MWG = NWAVES * 32 * NCB;
   constexpr int KSTR = T::KSTR, VSTR = T::VSTR;
-  constexpr int PIECES = KT * D / 8;             // 16-byte pieces per tile
-  constexpr int PPT = PIECES / NT;               // pieces per thread
-  constexpr int PPR = D / 8;                     // pieces per row
-  static_assert(PIECES % NT == 0, "tile must divide over the threads");
-  // double-buffered tiles: K(j) in s_k[j%2], V(j) in s_v[j%2]
-  extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
+  constexpr int PPR = D / 8;                     // 16-byte pieces per row
+  constexpr int TILE = KT * D;                   // elements of one K or V tile (unpadded, swizzled rows)
+  constexpr int NCHUNK = TILE * 2 / 1024;        // 1 KiB chunks (= wave-level loads) per tile
+  constexpr int CPW = NCHUNK / NWAVES;           // chunks per wave and tile
+  constexpr int RPC = 1024 / (D * 2);            // rows per chunk
+  static_assert(NCHUNK % NWAVES == 0, "tile must divide over the waves");
+  // double-buffered tiles: K(j) in s_k[j%2], V(j) in s_v[j%2]; then (8-wave workgroups only: they own the CU's LDS
+  // anyway) a separate region for the Q hand-over, so that the first tiles can be in flight while Q is staged
+  extern __shared__ __attribute__((aligned(1024))) uint16_t smem[];
   uint16_t* s_k = smem;
-  uint16_t* s_v = smem + 2 * KT * KSTR;
+  uint16_t* s_v = smem + 2 * TILE;
+  constexpr bool kQSeparate = NWAVES == 8;
+  uint16_t* s_q = kQSeparate ? smem + 4 * TILE : smem;
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, G = lane >> 5, n32 = lane & 31;
 
@@ -354,36 +376,50 @@ k_beam_attn(AttnCtx c) {
 #pragma unroll
   for (int cb = 0; cb < NCB; cb++) { m_run[cb] = -INFINITY; l_run[cb] = 0.f; }
 
-  // ---- K/V tile staging: global -> registers (one tile ahead) -> LDS
-  // Tiles are fetched with buffer loads: the descriptor (scalar registers) is rebuilt per tile from
-  // the tile's first row and the bytes left in the segment, the per-thread offsets never change, and
-  // rows past the end of the segment come back as zeros from the hardware range check (the -inf
-  // score mask on the K side and zero probabilities on the V side make them irrelevant).
+  // ---- K/V tile staging: global -> LDS directly (no registers, no LDS store instructions).  Wave w fills chunks
+  // w, w + NWAVES, ... of a tile: lane l of chunk ch writes LDS bytes 1024 ch + 16 l, i.e. slot l % PPR of row
+  // ch * RPC + l / PPR, and therefore fetches piece slot ^ swz(row) of that row.  Rows past the end of the segment
+  // (last tile only) re-read the last valid row: finite values that the -inf score mask (K) and zero probabilities
+  // (V) make irrelevant.  The loads are issued from inline assembly so that the compiler, which cannot tell the
+  // tile buffers apart, does not make every later LDS read wait for them; `tiles_landed` waits for all of this
+  // wave's loads, and the barrier that follows publishes every wave's.
   const uint32_t tok_bytes = (uint32_t)c.Hkv * D * 2;       // bytes between consecutive tokens
   const char* kbase = (const char*)c.ks + ((size_t)row0 * c.Hkv + kvh) * D * 2;
   const char* vbase = (const char*)c.vs + ((size_t)row0 * c.Hkv + kvh) * D * 2;
-  struct Stage { uint4 r[PPT]; };
-  Stage kreg, vreg;
-  constexpr int RPI = NT / PPR;                              // piece i of a thread sits RPI rows below piece i-1
-  const int prow0 = tid / PPR, pcol0 = (tid % PPR) * 8;
-  const uint32_t voff0 = (uint32_t)prow0 * tok_bytes + (uint32_t)pcol0 * 2;
-  auto gload = [&](const char* base, int t) {
-    const int tok0 = seg0 + t * KT;                                          // wave-uniform
-    const char* tile = base + (size_t)tok0 * tok_bytes;
-    const uint32_t left = (uint32_t)(seg1 - tok0 - 1) * tok_bytes + D * 2;   // up to the end of the last valid row
-    const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)tile, 0, left, 0x00020000);
-    Stage st;
+  const typename T::Rd rdo = T::make_rd(lane);
+  const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+  int crow[CPW];                                             // this lane's row inside a tile, per chunk
+  uint32_t koff[CPW], voff[CPW];                             // and its byte offsets from the tile's first row (full tiles)
 #pragma unroll
-    for (int i = 0; i < PPT; i++) {
-      const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rsrc, voff0 + (uint32_t)(i * RPI) * tok_bytes, 0, 0);
-      st.r[i] = make_uint4(v.x, v.y, v.z, v.w);
+  for (int i = 0; i < CPW; i++) {
+    const int ch = i * NWAVES + wave, row = ch * RPC + lane / PPR, slot = lane % PPR;
+    crow[i] = row;
+    koff[i] = (uint32_t)row * tok_bytes + (uint32_t)((slot ^ T::swz_k(row)) * 16);
+    voff[i] = (uint32_t)row * tok_bytes + (uint32_t)((slot ^ T::swz_v(row)) * 16);
+  }
+  const uint32_t lds_k = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint16_t*)s_k;
+  const uint32_t lds_v = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint16_t*)s_v;
+  auto dma = [&](uint32_t lds_addr, const char* gbase, uint32_t off) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_addr), "v"(off), "s"(gbase) : "memory", "m0");
+  };
+  auto tload = [&](bool is_k, int buf, int t) {
+    const int tok0 = seg0 + t * KT;                          // wave-uniform
+    const char* tile = (is_k ? kbase : vbase) + (size_t)tok0 * tok_bytes;
+    const uint32_t lds0 = (is_k ? lds_k : lds_v) + (uint32_t)buf * (TILE * 2);
+    const int nvalid = seg1 - tok0;                          // >= 1
+    if (nvalid >= KT) {
+#pragma unroll
+      for (int i = 0; i < CPW; i++) dma(lds0 + (uint32_t)(i * NWAVES + wave_u) * 1024, tile, is_k ? koff[i] : voff[i]);
+    } else {
+#pragma unroll
+      for (int i = 0; i < CPW; i++) {
+        const int row = min(crow[i], nvalid - 1), slot = lane % PPR;
+        const uint32_t off = (uint32_t)row * tok_bytes + (uint32_t)((slot ^ (is_k ? T::swz_k(crow[i]) : T::swz_v(crow[i]))) * 16);
+        dma(lds0 + (uint32_t)(i * NWAVES + wave_u) * 1024, tile, off);
+      }
     }
-    return st;
   };
-  auto lstore = [&](uint16_t* dst, int stride, const Stage& st) {
-#pragma unroll
-    for (int i = 0; i < PPT; i++) *(uint4*)(&dst[(prow0 + i * RPI) * stride + pcol0]) = st.r[i];
-  };
+  auto tiles_landed = [&]() { __builtin_amdgcn_s_waitcnt(0x0F70); };     // vmcnt(0)
 
   // ---- geometry of the unshared stage (segment 0 only): every beam's own u decode tokens go through
   // the same MFMA path as the prompt.  The 32 query columns of a wave belong to a handful of beams
@@ -435,11 +471,10 @@ k_beam_attn(AttnCtx c) {
     }
   };
 
-  // first prompt tiles: requested before anything waits on memory
-  Stage k1;
-  if (ntiles > 0) {
-    kreg = gload(kbase, 0); vreg = gload(vbase, 0);
-    k1 = gload(kbase, min(1, ntiles - 1));
+  // first prompt tiles: requested before anything waits on memory (when Q has its own LDS region)
+  if (kQSeparate && ntiles > 0) {
+    tload(true, 0, 0); tload(false, 0, 0);
+    tload(true, 1, min(1, ntiles - 1));
   }
   // Q as B operands: lane holds query column n32 of the wave's block, d = 16*ks + 8*G + (0..7)
   bf16x8 qop[NCB][D / 16];
@@ -447,12 +482,18 @@ k_beam_attn(AttnCtx c) {
 #pragma unroll
     for (int i = 0; i < QP; i++) {
       const int p = tid + i * NT, rl = p / PPR, col = (p % PPR) * 8;
-      *(uint4*)(&smem[rl * KSTR + col]) = qpiece[i];
+      *(uint4*)(&s_q[rl * KSTR + col]) = qpiece[i];
     }
     __syncthreads();
 #pragma unroll
-    for (int ks = 0; ks < D / 16; ks++) qop[0][ks] = as_bf16x8(*(const uint4*)(&smem[(wave * 32 + n32) * KSTR + ks * 16 + G * 8]));
-    __syncthreads();                                 // the tile slots may now be overwritten
+    for (int ks = 0; ks < D / 16; ks++) qop[0][ks] = as_bf16x8(*(const uint4*)(&s_q[(wave * 32 + n32) * KSTR + ks * 16 + G * 8]));
+    if (!kQSeparate) {
+      __syncthreads();                               // the tile slots may now be overwritten
+      if (ntiles > 0) {
+        tload(true, 0, 0); tload(false, 0, 0);
+        tload(true, 1, min(1, ntiles - 1));
+      }
+    }
   }
 
   if (ntiles > 0) {
@@ -461,11 +502,8 @@ k_beam_attn(AttnCtx c) {
     // barrier per tile orders every buffer reuse.  Loads for tiles past the end are clamped to the
     // last tile (harmless re-reads; a duplicate K tile lands in a buffer nobody reads any more).
     const int tl = ntiles - 1;
-    lstore(s_k, KSTR, kreg); lstore(s_v, VSTR, vreg);
-    lstore(s_k + KT * KSTR, KSTR, k1);
-    kreg = gload(kbase, min(2, tl));
-    vreg = gload(vbase, min(1, tl));
-    __syncthreads();
+    tiles_landed();
+    __syncthreads();                                   // K(0), V(0), K(1) are in LDS
 
     auto rescale = [&](const float (&alpha)[NCB], const bool (&upd)[NCB]) {
 #pragma unroll
@@ -505,15 +543,15 @@ k_beam_attn(AttnCtx c) {
         l_run[0] *= alpha;
         m_run[0] = m_new;
       }
-      __syncthreads();
-      lstore(s_k + (t & 1) * KT * KSTR, KSTR, kreg);                 // K(t+2)
-      lstore(s_v + ((t + 1) & 1) * KT * VSTR, VSTR, vreg);           // V(t+1)
-      kreg = gload(kbase, min(t + 3, tl));
-      vreg = gload(vbase, min(t + 2, tl));
-      T::fused(s_k + ((t + 1) & 1) * KT * KSTR, s_v + (t & 1) * KT * VSTR, qop, s_in, s_out, o_acc, m_run[0] * c.c, c.c, l_run[0], mx_cur, lane);
+      tiles_landed();                                               // this wave's K(t+1) and V(t) loads (issued one step ago)
+      __syncthreads();                                              // everyone's; and everyone is done with K(t) and V(t-1)
+      tload(true, t & 1, min(t + 2, tl));                           // K(t+2) over K(t)
+      tload(false, (t + 1) & 1, min(t + 1, tl));                    // V(t+1) over V(t-1)
+      T::fused(s_k + ((t + 1) & 1) * TILE, s_v + (t & 1) * TILE, qop, s_in, s_out, o_acc, m_run[0] * c.c, c.c, l_run[0], mx_cur, rdo);
     };
     // the last tile of the segment: the only one that can be partial, and it has no successor
     auto last = [&](f32x16 (&s_in)[KT / 32][NCB], int t) {
+      tiles_landed();
       if (own_stage) uload(0);
       __syncthreads();
       const int tok0 = seg0 + t * KT;
@@ -533,11 +571,11 @@ k_beam_attn(AttnCtx c) {
       bool upd[NCB];
       T::softmax(s_in, pop, m_run, l_run, alpha, upd, c.c);
       rescale(alpha, upd);
-      T::pv(s_v + (t & 1) * KT * VSTR, pop, o_acc, lane);
+      T::pv(s_v + (t & 1) * TILE, pop, o_acc, rdo);
     };
 
     f32x16 s_a[KT / 32][NCB], s_b[KT / 32][NCB];      // ping-pong score accumulators: no copies
-    T::qk(s_k, qop, s_a, n32, G);
+    T::qk(s_k, qop, s_a, rdo);
     if (ntiles > 1) mx_cur = T::colmax(s_a);
     // ntiles - 1 steps, then the last tile.  An odd step is peeled off first so that the loop runs
     // whole ping-pong pairs and the last tile is always in s_a.
@@ -771,6 +809,17 @@ __global__ void __launch_bounds__(256) k_attn_order(const int32_t* cu, int B, in
 // merge kernel, so it only pays while it fills idle CUs: segments are added until about one
 // workgroup per CU exists (never fewer than four tiles per segment), and not at all once 256 units
 // exist without it.
+// Dynamic LDS of k_beam_attn: K and V tiles, double-buffered (unpadded); the Q hand-over / output staging (padded rows),
+// behind the tiles for 256-row workgroups and on top of them for 128-row ones; one padded 32-row K and V mini-tile per
+// wave for the own-token stage (on top of everything else, after the prompt loop).
+size_t attn_lds_bytes(int d, int mwg) {
+  const size_t tiles = (size_t)4 * KT * d * 2;
+  const size_t rows = (size_t)mwg * (d + 8) * 2;
+  const size_t main_loop = mwg == 256 ? tiles + rows : (tiles > rows ? tiles : rows);
+  const size_t own = (size_t)(mwg / 32) * 32 * ((d + 8) + (d + 32)) * 2;
+  return main_loop > own ? main_loop : own;
+}
+
 struct AttnPlan { int mwg, nsplit; };
 int g_plan_rows = 0, g_plan_segments = 0;                  // gr_diag_attn_plan: 0 = use the rule below
 AttnPlan plan_attn(const gr_attn_params* p) {
@@ -873,9 +922,7 @@ extern "C" gr_status gr_beam_attn(const gr_attn_params* p, void* workspace, size
   const int64_t groups_padded = ((int64_t)c.n_groups + 7) / 8 * 8;
   const int64_t grid = groups_padded * c.MB;
   if (grid >= ((int64_t)1 << 31)) return GR_ERR_UNSUPPORTED;
-  const size_t lds_tiles = (size_t)2 * KT * ((p->d + 8) + (p->d + 32)) * 2;            // K and V tiles, double-buffered, padded rows
-  const size_t lds_own = (size_t)(plan.mwg / 32) * 32 * ((p->d + 8) + (p->d + 32)) * 2;  // one 32-row K and V mini-tile per wave
-  const size_t lds = lds_tiles > lds_own ? lds_tiles : lds_own;
+  const size_t lds = attn_lds_bytes(p->d, plan.mwg);
 #define GR_LAUNCH_ATTN(DD, NCB_, NW_)                                                                                        \
   do {                                                                                                                       \
     GR_HIP_TRY(hipFuncSetAttribute((const void*)k_beam_attn<DD, NCB_, NW_, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)); \
@@ -929,9 +976,7 @@ extern "C" gr_status gr_prefill_attn(const gr_prefill_params* p, void* stream_) 
   const int64_t groups_padded = ((int64_t)c.n_groups + 7) / 8 * 8;
   const int64_t grid = groups_padded * c.MB;
   if (grid >= ((int64_t)1 << 31)) return GR_ERR_UNSUPPORTED;
-  const size_t lds_tiles = (size_t)2 * KT * ((p->d + 8) + (p->d + 32)) * 2;
-  const size_t lds_out = (size_t)mwg * (p->d + 8) * 2;        // Q staging and the output staging of the epilogue
-  const size_t lds = lds_tiles > lds_out ? lds_tiles : lds_out;
+  const size_t lds = attn_lds_bytes(p->d, mwg);
 #define GR_LAUNCH_PREFILL(DD, NW_)                                                                                              \
   do {                                                                                                                         \
     GR_HIP_TRY(hipFuncSetAttribute((const void*)k_beam_attn<DD, 1, NW_, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)); \
