@@ -76,10 +76,11 @@ def test_noalloc_matches_workspace_entry_point_on_two_calls_in_a_row():
         want, got = _outputs(torch, B, W, 3, dev), _outputs(torch, B, W, 3, dev)
         assert lib.gr_beam_select(ctypes.byref(_params(m, logits, sc, pf, rg, step, want)), ctypes.c_void_p(ws.data_ptr()), need, stream) == 0
         torch.cuda.synchronize()
-        before = torch.cuda.memory_allocated()
+        # the caching allocator's count of allocations made so far (frees by Python's garbage collector do not touch it)
+        before = torch.cuda.memory_stats()["allocation.all.allocated"]
         assert lib.gr_beam_select_noalloc(ctypes.byref(_params(m, logits, sc, pf, rg, step, got)), stream) == 0
         torch.cuda.synchronize()
-        assert torch.cuda.memory_allocated() == before
+        assert torch.cuda.memory_stats()["allocation.all.allocated"] == before
         for k in want:
             assert torch.equal(got[k], want[k]), f"B={B} W={W} V={V}: {k} differs between the two entry points"
         assert bool((got["parent"] >= 0).all())
