@@ -803,12 +803,6 @@ __global__ void __launch_bounds__(256) k_attn_order(const int32_t* cu, int B, in
   }
 }
 
-// Host-side launch plan, fitted to a measured sweep over (B, L, W) on the MI355X.  8-wave workgroups
-// of 256 query rows stage each K/V tile once per 256 rows and win whenever a (request, KV head) has
-// more than 128 rows.  Splitting the prompt into L segments costs fp32 partials through HBM plus the
-// merge kernel, so it only pays while it fills idle CUs: segments are added until about one
-// workgroup per CU exists (never fewer than four tiles per segment), and not at all once 256 units
-// exist without it.
 // Dynamic LDS of k_beam_attn: K and V tiles, double-buffered (unpadded); the Q hand-over / output staging (padded rows),
 // behind the tiles for 256-row workgroups and on top of them for 128-row ones; one padded 32-row K and V mini-tile per
 // wave for the own-token stage (on top of everything else, after the prompt loop).
@@ -820,6 +814,13 @@ size_t attn_lds_bytes(int d, int mwg) {
   return main_loop > own ? main_loop : own;
 }
 
+// Host-side launch plan, fitted to a measured sweep over (B, L, W) on the MI355X.  8-wave workgroups
+// of 256 query rows stage each K/V tile once per 256 rows and win once there are at least 256 of them
+// (one per CU); below that, 4-wave workgroups of 128 rows (two fit a CU) fill the chip better than
+// splitting the prompt further.  Splitting the prompt into L segments costs fp32 partials through HBM
+// plus the merge kernel, so it only pays while it fills idle CUs: segments are added until about one
+// workgroup per CU exists (never fewer than four tiles per segment), and not at all once 256 units
+// exist without it.
 struct AttnPlan { int mwg, nsplit; };
 int g_plan_rows = 0, g_plan_segments = 0;                  // gr_diag_attn_plan: 0 = use the rule below
 AttnPlan plan_attn(const gr_attn_params* p) {
@@ -832,7 +833,8 @@ AttnPlan plan_attn(const gr_attn_params* p) {
     plan.nsplit = (int)(g_plan_segments < cap ? g_plan_segments : (cap < 1 ? 1 : cap));
     return plan;
   }
-  plan.mwg = M <= 128 ? 128 : 256;
+  const int64_t units256 = (int64_t)p->B * p->Hkv * ((M + 255) / 256);
+  plan.mwg = (M <= 128 || units256 < 256) ? 128 : 256;     // 256-row workgroups only when they fill the chip by themselves
   const int64_t units = (int64_t)p->B * p->Hkv * ((M + plan.mwg - 1) / plan.mwg);
   plan.nsplit = 1;
   if (units < 256 && p->max_L > 4 * KT) {
