@@ -11,6 +11,7 @@ measured machine peaks).
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 3] [--no-cpu-baseline]
     python bench.py --sweep-attn-plan        # the (B, L, W) x (row tile, L segments) table the launch rule is fitted to
+    python bench.py --issue-test             # how much VALU work hides behind MFMAs on this chip (attention roofline discussion)
 """
 import argparse
 import json
@@ -68,6 +69,27 @@ def measured_peaks(torch, gr, dev):
     ms = _elapsed(torch, lambda: gr.gr_diag_mfma_loop(ops, wgs, iters, sink), 10)
     return dict(hbm_read_GBps=round(read_gbs, 1), bf16_mfma_TFLOPs=round(flops / (ms * 1e-3) / 1e12, 1),
                 how="plain 16-byte-load read of 1 GiB; 1024 workgroups x 8 waves of back-to-back 32x32x16 bf16 MFMAs on N(0,1) operands, both after the clock has settled")
+
+
+def issue_test(torch, gr, dev):
+    """How much vector work hides behind matrix instructions on one SIMD: time per slot of { MFMA, n FMA, m exp } per wave,
+    for two and four waves per SIMD (nanoseconds per slot and SIMD; the MFMA-only row is the matrix pipe's own rate)."""
+    sink = torch.zeros(4, dtype=torch.float32, device=dev)
+    ops = (torch.randn(8192, dtype=torch.float32, device=dev) * 0.01).to(torch.bfloat16)
+    iters = 2048
+    combos = [(1, 0, 0), (1, 2, 0), (1, 4, 0), (1, 8, 0), (1, 12, 0), (1, 0, 1), (1, 2, 1), (1, 3, 1), (1, 4, 1), (1, 4, 2),
+              (0, 4, 0), (0, 12, 0), (0, 0, 1), (0, 0, 4), (0, 4, 1)]
+    print("mfma n_fma n_exp | ns per slot and SIMD: 2 waves/SIMD  4 waves/SIMD")
+    for mf, nv, nx in combos:
+        cells = []
+        for wgs in (256, 512):
+            run = lambda: gr.gr_diag_issue_loop(ops, wgs, iters, nv, nx, mf, sink)
+            for _ in range(3):
+                run()
+            ms = _elapsed(torch, run, 5)
+            slots = wgs * 8 / 1024 * iters * 4
+            cells.append(f"{ms * 1e6 / slots:6.1f}")
+        print(f"{mf:4d} {nv:5d} {nx:5d} | {cells[0]}  {cells[1]}", flush=True)
 
 
 def sweep_attn_plan(torch, gr, dev):
@@ -132,6 +154,7 @@ def main():
                     help="also run one plain 1 GiB device copy (known HBM traffic) so that rocprofv3 FETCH_SIZE / WRITE_SIZE "
                          "readings of the same run can be scaled")
     ap.add_argument("--sweep-attn-plan", action="store_true", help="print the launch-plan sweep table and exit")
+    ap.add_argument("--issue-test", action="store_true", help="print the MFMA / VALU issue test table and exit")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; requests are independent and would shard across GPUs with no exchange, "
@@ -152,6 +175,9 @@ def main():
     torch.cuda.set_device(dev)
     if args.sweep_attn_plan:
         sweep_attn_plan(torch, gr, dev)
+        return
+    if args.issue_test:
+        issue_test(torch, gr, dev)
         return
     cfg = gr_synth.get_config(args.config)
     B, W, V, ND, Hq, Hkv, d = cfg.B, cfg.W, cfg.V, cfg.ND, cfg.Hq, cfg.Hkv, cfg.d

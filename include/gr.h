@@ -239,8 +239,15 @@ gr_status gr_beam_reorder(int32_t B, int32_t W, int32_t ND, int32_t Hkv, int32_t
  *   workgroups of `rows_per_workgroup` (128 or 256) query rows and `l_segments` (1..16, lowered to the number of
  *   K/V tiles in the longest prompt) prompt segments instead of the built-in launch rule; (0, 0) restores the rule.
  *   For sweeps that refit the rule; not thread-safe against concurrent gr_beam_attn calls.
+ * gr_diag_issue_loop: the issue test behind the attention kernel's roofline discussion.  `workgroups` x 8 wavefronts
+ *   (256 workgroups = two wavefronts per SIMD, 512 = four) each run `iters` x 4 slots of { one bf16 32x32x16 MFMA if
+ *   `with_mfma`, `n_fma` independent fp32 FMAs, `n_exp` v_exp_f32 }.  Built combinations (n_fma, n_exp): (0,0) (2,0)
+ *   (4,0) (8,0) (12,0) (0,1) (2,1) (3,1) (4,1) (4,2) (0,4); others return UNSUPPORTED.  Operands and sink as for
+ *   gr_diag_mfma_loop.
  * Errors: INVALID_ARG, UNSUPPORTED, HIP.
  * ------------------------------------------------------------------------------------------------ */
+gr_status gr_diag_issue_loop(const void* operands, int32_t workgroups, int32_t iters, int32_t n_fma, int32_t n_exp,
+                             int32_t with_mfma, void* sink, void* stream);
 gr_status gr_diag_attn_plan(int32_t rows_per_workgroup, int32_t l_segments);
 gr_status gr_diag_stream_read(const void* src, size_t bytes, void* sink, void* stream);
 gr_status gr_diag_mfma_loop(const void* operands, int32_t workgroups, int32_t iters, void* sink, void* stream);

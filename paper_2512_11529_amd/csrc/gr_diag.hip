@@ -44,7 +44,68 @@ __global__ void __launch_bounds__(512) k_diag_mfma(const uint4* operands, int it
   if (s == 12345.678f) sink[0] = s;
 }
 
+// Issue test: how much vector work hides behind matrix instructions on one SIMD.  Each wavefront iterates
+// { one MFMA (four independent accumulator tiles in turn), NV independent fp32 FMAs, NX v_exp_f32 }, in that order.
+template <int NV, int NX, bool MFMA>
+__global__ void __launch_bounds__(512) k_diag_issue(const uint4* operands, int iters, float* sink) {
+  const int lane = threadIdx.x & 63;
+  const bf16x8 a = __builtin_bit_cast(bf16x8, operands[threadIdx.x]), b = __builtin_bit_cast(bf16x8, operands[512 + threadIdx.x]);
+  f32x16 acc[kAcc];
+#pragma unroll
+  for (int k = 0; k < kAcc; k++)
+#pragma unroll
+    for (int i = 0; i < 16; i++) acc[k][i] = 0.f;
+  float v[8], x[4];
+#pragma unroll
+  for (int i = 0; i < 8; i++) v[i] = (float)(lane + i) * 1e-3f;
+#pragma unroll
+  for (int i = 0; i < 4; i++) x[i] = (float)(lane + i) * 1e-4f;
+  for (int it = 0; it < iters; it++) {
+#pragma unroll
+    for (int k = 0; k < kAcc; k++) {
+      if (MFMA) acc[k] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[k], 0, 0, 0);
+#pragma unroll
+      for (int n = 0; n < NV; n++) v[n % 8] = fmaf(v[n % 8], 1.0001f, 1e-6f);
+#pragma unroll
+      for (int n = 0; n < NX; n++) x[n % 4] = __builtin_amdgcn_exp2f(x[n % 4]) * 1e-3f;
+      asm volatile("" : "+v"(v[0]), "+v"(v[1]), "+v"(v[2]), "+v"(v[3]), "+v"(v[4]), "+v"(v[5]), "+v"(v[6]), "+v"(v[7]),
+                        "+v"(x[0]), "+v"(x[1]), "+v"(x[2]), "+v"(x[3]));
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
+  float s = 0.f;
+#pragma unroll
+  for (int k = 0; k < kAcc; k++)
+#pragma unroll
+    for (int i = 0; i < 16; i++) s += acc[k][i];
+#pragma unroll
+  for (int i = 0; i < 8; i++) s += v[i];
+#pragma unroll
+  for (int i = 0; i < 4; i++) s += x[i];
+  if (s == 12345.678f) sink[0] = s;
+}
+
 }  // namespace
+
+extern "C" gr_status gr_diag_issue_loop(const void* operands, int32_t workgroups, int32_t iters, int32_t n_fma, int32_t n_exp,
+                                        int32_t with_mfma, void* sink, void* stream_) {
+  if (!operands || !sink || workgroups <= 0 || iters <= 0 || ((uintptr_t)operands & 15)) return GR_ERR_INVALID_ARG;
+  const uint4* ops = (const uint4*)operands;
+  float* sk = (float*)sink;
+  hipStream_t st = (hipStream_t)stream_;
+  const dim3 g((unsigned)workgroups), b(512);
+#define GR_ISSUE(NV_, NX_)                                                                                 \
+  if (n_fma == NV_ && n_exp == NX_) {                                                                      \
+    if (with_mfma) hipLaunchKernelGGL((k_diag_issue<NV_, NX_, true>), g, b, 0, st, ops, iters, sk);        \
+    else hipLaunchKernelGGL((k_diag_issue<NV_, NX_, false>), g, b, 0, st, ops, iters, sk);                 \
+    GR_HIP_TRY(hipGetLastError());                                                                         \
+    return GR_OK;                                                                                          \
+  }
+  GR_ISSUE(0, 0) GR_ISSUE(2, 0) GR_ISSUE(4, 0) GR_ISSUE(8, 0) GR_ISSUE(12, 0)
+  GR_ISSUE(0, 1) GR_ISSUE(2, 1) GR_ISSUE(3, 1) GR_ISSUE(4, 1) GR_ISSUE(4, 2) GR_ISSUE(0, 4)
+#undef GR_ISSUE
+  return GR_ERR_UNSUPPORTED;
+}
 
 extern "C" gr_status gr_diag_stream_read(const void* src, size_t bytes, void* sink, void* stream_) {
   if (!src || !sink || bytes < ((size_t)1 << 20) || ((uintptr_t)src & 15)) return GR_ERR_INVALID_ARG;
