@@ -120,3 +120,21 @@ def test_argument_errors(gr):
     with pytest.raises(gr.GrError) as e:
         run_attn(gr, a, 1.0)
     assert e.value.status == -1
+
+
+@pytest.mark.parametrize("d", [64, 128])
+@pytest.mark.parametrize("rows,segments", [(128, 1), (256, 1), (128, 3), (256, 2), (256, 16)])
+def test_every_launch_plan_matches_oracle(gr, oracle_lib, d, rows, segments):
+    """Both workgroup sizes and the L-split path of both head sizes, forced through the plan override (the built-in rule
+    picks only one of them per shape): ragged batch, 640 query rows per KV head, a prompt that ends inside a tile."""
+    B, W, Hq, Hkv = 2, 160, 8, 2
+    a = rand_attn_case(50 + d + rows + segments, B, W, Hq, Hkv, d, 3, 2, (333, 1100))
+    rng = np.random.default_rng(4)
+    n = 240
+    tri = np.stack([rng.integers(0, B, n), rng.integers(0, W, n), rng.integers(0, Hq, n)], axis=1).astype(np.int32)
+    tri[:6] = [[0, 0, 0], [1, W - 1, Hq - 1], [0, 31, 3], [1, 32, 4], [0, 63, 7], [1, 64, 0]]
+    gr.gr_diag_attn_plan(rows, segments)
+    try:
+        _check(gr, oracle_lib, a, float(np.float32(1 / np.sqrt(d))), tri)
+    finally:
+        gr.gr_diag_attn_plan(0, 0)
