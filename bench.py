@@ -71,6 +71,26 @@ def measured_peaks(torch, gr, dev):
                 how="plain 16-byte-load read of 1 GiB; 1024 workgroups x 8 waves of back-to-back 32x32x16 bf16 MFMAs on N(0,1) operands, both after the clock has settled")
 
 
+def summarize_trace(path):
+    """Mean kernel duration per decode level over the last 60 steps of a rocprofv3 kernel-trace CSV of this benchmark
+    (run with --no-extras: the trace then ends with the timed steps, each = k_beam_attn, k_rows, k_select)."""
+    import collections
+    import csv
+    rows = [r for r in csv.DictReader(open(path)) if any(k in r["Kernel_Name"] for k in ("k_rows", "k_select", "k_beam_attn"))]
+    rows.sort(key=lambda r: int(r["Start_Timestamp"]))
+    seq = [("k_rows" if "k_rows" in r["Kernel_Name"] else "k_select" if "k_select" in r["Kernel_Name"] else "k_beam_attn",
+            int(r["End_Timestamp"]) - int(r["Start_Timestamp"])) for r in rows][-180:]
+    acc = collections.defaultdict(list)
+    for i in range(0, len(seq) - 2, 3):
+        trio = seq[i:i + 3]
+        if [t[0] for t in trio] != ["k_beam_attn", "k_rows", "k_select"]:
+            raise SystemExit(f"unexpected kernel order at {i}: {trio}")
+        for name, dur in trio:
+            acc[((i // 3) % 3, name)].append(dur)
+    for name in ("k_beam_attn", "k_rows", "k_select"):
+        print(f"{name:12s} " + "   ".join(f"level{lvl} {sum(acc[(lvl, name)]) / max(len(acc[(lvl, name)]), 1) / 1e3:7.1f} us" for lvl in range(3)))
+
+
 def issue_test(torch, gr, dev):
     """How much vector work hides behind matrix instructions on one SIMD: time per slot of { MFMA, n FMA, m exp } per wave,
     for two and four waves per SIMD (nanoseconds per slot and SIMD; the MFMA-only row is the matrix pipe's own rate)."""
@@ -155,7 +175,12 @@ def main():
                          "readings of the same run can be scaled")
     ap.add_argument("--sweep-attn-plan", action="store_true", help="print the launch-plan sweep table and exit")
     ap.add_argument("--issue-test", action="store_true", help="print the MFMA / VALU issue test table and exit")
+    ap.add_argument("--summarize-trace", metavar="CSV", help="per-level kernel means from a rocprofv3 kernel-trace CSV of this benchmark "
+                                                              "(made with --kernel-trace --output-format csv ... --no-extras), then exit; needs no GPU")
     args = ap.parse_args()
+    if args.summarize_trace:
+        summarize_trace(args.summarize_trace)
+        return
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; requests are independent and would shard across GPUs with no exchange, "
               "so --gpus must be 1", file=sys.stderr)
@@ -360,6 +385,29 @@ def main():
             gms = _elapsed(torch, g.replay, cycles) / ND
             same = all(bool(torch.equal(ref[k], buf["sel_out"][ND - 1][k])) for k in ref)
             graph = dict(ms_per_step=round(gms, 4), steps_per_s=round(1000.0 / gms, 3), cycles=cycles, replay_matches_eager=same)
+            # the same cycle with the cache move between the item step and the next attention (attn -> select -> reorder)
+            ku_g = [attn_in[s]["ku"].clone() for s in range(ND)]
+            vu_g = [attn_in[s]["vu"].clone() for s in range(ND)]
+
+            def full_cycle():
+                for s in range(ND):
+                    a = attn_in[s]
+                    gr.gr_beam_attn(a["q"], k_sh, v_sh, d_cu, ku_g[s], vu_g[s], a["u"], scale, max_L, total_L, out=buf["out"], workspace=buf["ws_attn"])
+                    select(s)
+                    gr.gr_beam_reorder(buf["sel_out"][s]["parent"], ku_g[s], vu_g[s], s + 1)
+            full_cycle()
+            torch.cuda.synchronize()
+            g2 = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g2):
+                full_cycle()
+            for _ in range(3):
+                g2.replay()
+            torch.cuda.synchronize()
+            gms2 = _elapsed(torch, g2.replay, cycles) / ND
+            eager2 = _elapsed(torch, full_cycle, cycles) / ND
+            graph["with_reorder"] = dict(graph_ms_per_step=round(gms2, 4), graph_steps_per_s=round(1000.0 / gms2, 3),
+                                         eager_ms_per_step=round(eager2, 4), eager_steps_per_s=round(1000.0 / eager2, 3))
+            del ku_g, vu_g
         except Exception as e:          # the headline above stands on its own
             graph = dict(error=f"{type(e).__name__}: {e}"[:300])
         # (3) two independent batches on two streams of equal priority (one stream per batch): aggregate rate
