@@ -173,6 +173,7 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (known HBM traffic) so that rocprofv3 FETCH_SIZE / WRITE_SIZE "
                          "readings of the same run can be scaled")
+    ap.add_argument("--layers", type=int, default=4, help="attention calls per decode step in the per-layer extra leg")
     ap.add_argument("--sweep-attn-plan", action="store_true", help="print the launch-plan sweep table and exit")
     ap.add_argument("--issue-test", action="store_true", help="print the MFMA / VALU issue test table and exit")
     ap.add_argument("--summarize-trace", metavar="CSV", help="per-level kernel means from a rocprofv3 kernel-trace CSV of this benchmark "
@@ -320,7 +321,7 @@ def main():
             sel_by_level[f"level{s}"] = dict(ms=round(float(np.mean(ms)), 4), live_rows=live_rows[s])
 
     # ---------------- extras, outside the headline's timed region
-    roofline_select, reorder, graph, streams, peaks, prefill = None, None, None, None, None, None
+    roofline_select, reorder, graph, streams, peaks, prefill, layers = None, None, None, None, None, None, None
     if not args.no_extras:
         # (0) the item step on its dense paths: every live row streamed in full (GR_SELECT_FORCE_DENSE, and mask = NULL),
         # on the levels where all B*W rows are live.  Algorithmic bytes = live rows x (4V logits + V/8 mask bits); the time
@@ -449,7 +450,36 @@ def main():
             del qp, op
         except Exception as e:
             prefill = dict(error=f"{type(e).__name__}: {e}"[:300])
-        # (5) what the machine sustains, next to the datasheet peaks
+        # (5) a per-layer loop: n_layers attention calls (each layer its own K/V and Q) + one item step per decode step,
+        # the three levels captured as one graph.  Layer count is a stand-in (no model geometry is given); what it shows
+        # is that the step scales by the attention time per layer with nothing added between the calls.
+        try:
+            n_layers = args.layers
+            lay = [dict(q=torch.randn_like(attn_in[0]["q"].float()).to(torch.bfloat16), ks=torch.randn_like(k_sh.float()).to(torch.bfloat16),
+                        vs=torch.randn_like(v_sh.float()).to(torch.bfloat16)) for _ in range(n_layers)]
+
+            def layered_cycle():
+                for s in range(ND):
+                    a = attn_in[s]
+                    for l in lay:
+                        gr.gr_beam_attn(l["q"], l["ks"], l["vs"], d_cu, a["ku"], a["vu"], a["u"], scale, max_L, total_L, out=buf["out"], workspace=buf["ws_attn"])
+                    select(s)
+            layered_cycle()
+            torch.cuda.synchronize()
+            g3 = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g3):
+                layered_cycle()
+            for _ in range(2):
+                g3.replay()
+            torch.cuda.synchronize()
+            cyc = max(1, K // (ND * n_layers))
+            lms = _elapsed(torch, g3.replay, cyc) / ND
+            layers = dict(n_layers=n_layers, graph_ms_per_step=round(lms, 4), steps_per_s=round(1000.0 / lms, 3),
+                          ms_per_layer=round((lms - float(np.mean(sel_ms))) / n_layers, 4), note="N(0,1) Q/K/V per layer; one item step per decode step")
+            del lay
+        except Exception as e:
+            layers = dict(error=f"{type(e).__name__}: {e}"[:300])
+        # (6) what the machine sustains, next to the datasheet peaks
         try:
             peaks = measured_peaks(torch, gr, dev)
             roofline["peak_measured"] = peaks["bf16_mfma_TFLOPs"]
@@ -494,7 +524,7 @@ def main():
         roofline=roofline, roofline_select=roofline_select, cpu_baseline=cpu,
         attn=dict(ms_by_u={f"u{s + 1}": round(float(np.mean([attn_ms[i] for i in range(K) if i % ND == s] or [0])), 4) for s in range(ND)},
                   tflops=round(attn_tflops, 2), ms_first20_after_idle=round(cold_ms, 4)),
-        select=sel_by_level, reorder=reorder, graph=graph, two_streams=streams, prefill=prefill, peaks_measured=peaks,
+        select=sel_by_level, reorder=reorder, graph=graph, two_streams=streams, prefill=prefill, layers=layers, peaks_measured=peaks,
         prewarm=dict(ms=args.prewarm_ms, steps=prewarm_steps), wall_s=round(wall, 3), input_gen_s=round(t_gen, 1))
     print(json.dumps(line))
 
