@@ -56,7 +56,8 @@ const char* gr_status_string(gr_status s);
  * merge combines the (max, sum, output) partials.  No causal mask is applied: every key precedes
  * or is the query position.
  *
- * Supported: d in {64, 128}; Hq % Hkv == 0; 1 <= u <= ND; L_b >= 0 (L_b + u >= 1).
+ * Supported: d in {64, 128}; Hq % Hkv == 0; 1 <= u <= ND; L_b >= 0 (L_b + u >= 1).  All bf16 tensors must be
+ * 16-byte aligned (INVALID_ARG otherwise) and hold finite values.
  * ------------------------------------------------------------------------------------------------ */
 typedef struct {
   int32_t B, W, Hq, Hkv, d;   /* requests, beam width, query heads, KV heads, head dim              */
@@ -96,7 +97,7 @@ gr_status gr_beam_attn(const gr_attn_params* p, void* workspace, size_t workspac
  * the tiles on the diagonal.  No workspace.  Only enqueues on `stream`; no synchronisation.
  *
  * Supported: d in {64, 128}; Hq % Hkv == 0; total_L < 2^31; max_L * Hq/Hkv < 2^22;
- * max_L * Hkv * d * 2 < 2^32; max_L * Hq * d < 2^31.
+ * max_L * Hkv * d * 2 < 2^32; max_L * Hq * d < 2^31.  All bf16 tensors 16-byte aligned.
  * ------------------------------------------------------------------------------------------------ */
 typedef struct {
   int32_t B, Hq, Hkv, d;

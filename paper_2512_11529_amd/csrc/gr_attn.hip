@@ -6,8 +6,8 @@
 // so that every lane owns ONE query column: the online-softmax max / sum / rescale are per-lane
 // scalars and the exponentiated scores leave the accumulators already in the B-operand layout of
 //     O^T[d, q] += V^T[d, kv] . P^T[kv, q]     (A = V tile read from LDS with the transposing ds_read_b64_tr_b16).
-// Each prompt K/V tile is staged once per workgroup (coalesced 16-byte loads -> padded LDS) and used
-// by all query rows of the block.  The unshared stage (each beam's own u decode tokens) and the merge
+// Each prompt K/V tile is brought in once per workgroup (direct global -> LDS loads into unpadded, XOR-swizzled
+// tiles) and used by all query rows of the block.  The unshared stage (each beam's own u decode tokens) and the merge
 // run in the epilogue of segment 0 on the same per-lane state; when the prompt is split into
 // segments, partial (max, sum, O) go to the workspace and k_attn_merge combines them.
 #include "gr_internal.hpp"
@@ -884,6 +884,9 @@ extern "C" gr_status gr_beam_attn(const gr_attn_params* p, void* workspace, size
   if (p->total_L > 0 && (!p->k_shared || !p->v_shared)) return GR_ERR_INVALID_ARG;
   if (p->u > 0 && (!p->k_unshared || !p->v_unshared)) return GR_ERR_INVALID_ARG;
   if (p->Hq % p->Hkv) return GR_ERR_INVALID_ARG;
+  if ((((uintptr_t)p->q | (uintptr_t)p->k_shared | (uintptr_t)p->v_shared | (uintptr_t)p->k_unshared | (uintptr_t)p->v_unshared |
+        (uintptr_t)p->out) & 15) || ((uintptr_t)p->cu_seqlens & 3) || ((uintptr_t)p->lse_out & 3))
+    return GR_ERR_INVALID_ARG;                                                          // every tensor is moved in 16-byte pieces
   if (!(p->sm_scale > 0.f) || !(p->sm_scale < INFINITY)) return GR_ERR_INVALID_ARG;   // (also rejects NaN: the lazy-maximum test assumes a positive scale)
   if (p->d != 64 && p->d != 128) return GR_ERR_UNSUPPORTED;
   if (p->total_L >= ((int64_t)1 << 31)) return GR_ERR_UNSUPPORTED;
@@ -954,6 +957,9 @@ extern "C" gr_status gr_prefill_attn(const gr_prefill_params* p, void* stream_) 
   if (p->max_L < 0 || p->total_L < 0 || p->total_L > (int64_t)p->max_L * p->B) return GR_ERR_INVALID_ARG;
   if (!p->cu_seqlens) return GR_ERR_INVALID_ARG;
   if (p->total_L > 0 && (!p->q || !p->k || !p->v || !p->out)) return GR_ERR_INVALID_ARG;
+  if ((((uintptr_t)p->q | (uintptr_t)p->k | (uintptr_t)p->v | (uintptr_t)p->out) & 15) || ((uintptr_t)p->cu_seqlens & 3) ||
+      ((uintptr_t)p->lse_out & 3))
+    return GR_ERR_INVALID_ARG;
   if (!(p->sm_scale > 0.f) || !(p->sm_scale < INFINITY)) return GR_ERR_INVALID_ARG;
   if (p->d != 64 && p->d != 128) return GR_ERR_UNSUPPORTED;
   if (p->total_L >= ((int64_t)1 << 31)) return GR_ERR_UNSUPPORTED;

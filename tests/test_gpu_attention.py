@@ -120,6 +120,16 @@ def test_argument_errors(gr):
     with pytest.raises(gr.GrError) as e:
         run_attn(gr, a, 1.0)
     assert e.value.status == -1
+    # a tensor that does not start on a 16-byte boundary is refused (the kernels move 16-byte pieces)
+    a = rand_attn_case(2, 1, 2, 2, 2, 64, 3, 1, (5,))
+    q = bf16_to_dev(a["q"])
+    shifted = torch.empty(q.numel() + 8, dtype=torch.bfloat16, device=q.device)[1:1 + q.numel()].view(q.shape)
+    shifted.copy_(q)
+    assert shifted.data_ptr() % 16 == 2
+    with pytest.raises(gr.GrError) as e:
+        gr.gr_beam_attn(shifted, bf16_to_dev(a["k_shared"]), bf16_to_dev(a["v_shared"]), to_dev(a["cu_seqlens"]),
+                        bf16_to_dev(a["k_unshared"]), bf16_to_dev(a["v_unshared"]), 1, 1.0, 5, 5)
+    assert e.value.status == -1
 
 
 @pytest.mark.parametrize("d", [64, 128])
