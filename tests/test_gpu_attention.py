@@ -87,6 +87,19 @@ def test_structured_inputs_give_order_one_outputs(gr, oracle_lib):
     _check(gr, oracle_lib, a, 1.0)
 
 
+def test_scores_rising_along_the_prompt_raise_the_reference_on_every_tile(gr, oracle_lib):
+    # keys proportional to one query with a factor that grows with the position: that query's scores climb by ~15 bits per
+    # 64-token tile (the lazily raised reference maximum and the O / row-sum rescale run on every tile), the last key
+    # dominates, and for the opposite sign the first tile holds the maximum and everything later underflows
+    B, W, Hq, Hkv, d, L = 1, 4, 4, 1, 64, 1000
+    for sign in (1.0, -1.0):
+        a = rand_attn_case(17, B, W, Hq, Hkv, d, 3, 2, (L,))
+        q0 = gr_synth.bf16_bits_to_f32(a["q"])[0, 0, 0]
+        ramp = (np.arange(L, dtype=np.float32) / 50.0)[:, None]
+        a["k_shared"][:, 0] = gr_synth.f32_to_bf16_bits(sign * ramp * q0[None, :])
+        _check(gr, oracle_lib, a, 0.125)
+
+
 def test_wide_beam_sampled_rows(gr, oracle_lib):
     # W = 2048 beams (8192 query rows per KV head, 32 row blocks): sampled outputs against the oracle
     B, W, Hq, Hkv, d = 1, 2048, 8, 2, 64
