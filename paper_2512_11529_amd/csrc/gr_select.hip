@@ -606,26 +606,29 @@ __device__ int radix_select_all(const SelCtx& c, const MaskView& mv, int b, uint
   return min((int)s_cnt, kListCap);
 }
 
-// Wave 0 only: smallest bin t with at least `want` entries in bins 0..t (bin 0 = best scores); the
-// last bin when there are fewer than `want` entries in total.
-__device__ __forceinline__ void hist_threshold(const uint32_t* s_hist, uint32_t want, int* s_thr) {
-  const int lane = threadIdx.x & 63;
-  constexpr int per = kHistBins / 64;
-  uint32_t local = 0;
-  for (int i = 0; i < per; i++) local += s_hist[lane * per + i];
-  uint32_t incl = local;   // inclusive prefix sum over lanes
-  for (int o = 1; o < 64; o <<= 1) {
-    uint32_t v = __shfl_up(incl, o, 64);
-    if (lane >= o) incl += v;
-  }
-  const uint32_t tot = __shfl(incl, 63, 64);
-  const uint32_t below = incl - local;
-  if (tot < want) {
-    if (lane == 0) *s_thr = kHistBins - 1;
-  } else if (below < want && want <= incl) {
+// Smallest bin t with at least `want` entries in bins 0..t (bin 0 = best scores); the last bin when there are fewer
+// than `want` entries in total.  Done by the whole workgroup (every thread owns kHistBins / kSelThreads consecutive
+// bins; one scan, one barrier inside): a serial walk by one wavefront over 32 bins per lane costs more than a
+// microsecond.  The caller puts a barrier behind it before reading *s_thr.
+__device__ __forceinline__ void hist_threshold_all(const uint32_t* s_hist, uint32_t want, int* s_thr, uint32_t* s_redu, int& par) {
+  constexpr int per = kHistBins / kSelThreads;
+  const int tid = threadIdx.x;
+  uint32_t h[per], local = 0;
+#pragma unroll
+  for (int k = 0; k < per; k++) { h[k] = s_hist[tid * per + k]; local += h[k]; }
+  uint32_t total;
+  const uint32_t below = block_excl_scan<kSelThreads / 64>(local, &total, s_redu, par);
+  if (total < want) {
+    if (tid == 0) *s_thr = kHistBins - 1;
+  } else if (below < want && want <= below + local) {
     uint32_t acc = below;
-    int bin = lane * per;
-    for (;; bin++) { acc += s_hist[bin]; if (acc >= want) break; }
+    int bin = tid * per;
+#pragma unroll
+    for (int k = 0; k < per; k++) {
+      acc += h[k];
+      if (acc >= want) break;
+      bin++;
+    }
     *s_thr = bin;
   }
 }
@@ -640,7 +643,9 @@ __global__ void __launch_bounds__(kSelThreads) k_select(SelCtx c) {
   int32_t* s_ra = s_rmode + kMaxW;                           // first token (step 1) or table range start (step 2),
   int32_t* s_rb = s_ra + kMaxW;                              // table range end (step 2)
   __shared__ float s_redf[kSelThreads / 64];
+  __shared__ uint32_t s_redu[2 * (kSelThreads / 64)];
   __shared__ uint16_t s_live[kMaxW];
+  int par = 0;
   __shared__ uint32_t s_n, s_nc, s_nlive;
   __shared__ int s_thr;
   const int b = blockIdx.x, tid = threadIdx.x;
@@ -717,7 +722,7 @@ __global__ void __launch_bounds__(kSelThreads) k_select(SelCtx c) {
       if (group_of(idx, &w, &g)) bin4(keys4[(size_t)w * (kChunksPerRow / 4) + g], [&](int, int bin) { atomicAdd(&s_hist[bin], 1u); });
     }
     __syncthreads();
-    if (tid < 64) hist_threshold(s_hist, (uint32_t)c.W, &s_thr);
+    hist_threshold_all(s_hist, (uint32_t)c.W, &s_thr, s_redu, par);
     __syncthreads();
     const int thr = s_thr;
     // ---- chunks that reach the threshold
@@ -848,7 +853,7 @@ __global__ void __launch_bounds__(kSelThreads) k_select(SelCtx c) {
       for (int k = 0; k < kListCap / kSelThreads; k++)
         if (tid + k * kSelThreads < n) atomicAdd(&s_hist[key_bin(top, gr_ordkey_inv((uint32_t)(mine[k] >> 32)))], 1u);
       __syncthreads();
-      if (tid < 64) hist_threshold(s_hist, (uint32_t)c.W, &s_thr);
+      hist_threshold_all(s_hist, (uint32_t)c.W, &s_thr, s_redu, par);
       __syncthreads();
       const int thr2 = s_thr;
 #pragma unroll
@@ -867,8 +872,6 @@ __global__ void __launch_bounds__(kSelThreads) k_select(SelCtx c) {
     // better bins plus its rank inside its own (tiny) bin.  Counting sort by bin into the upper half of the list,
     // then every survivor counts the larger keys of its bin.  Exact ties share a bin and are ranked by the key's
     // flat-index half there.
-    __shared__ uint32_t s_redu[2 * NW];
-    int par = 0;
     float top = -INFINITY, bottom = INFINITY;
     for (int i = tid; i < n; i += kSelThreads) { const float sc = gr_ordkey_inv((uint32_t)(s_list[i] >> 32)); top = fmaxf(top, sc); bottom = fminf(bottom, sc); }
     top = block_max2<NW>(top, s_redf);
