@@ -14,7 +14,9 @@ random: Q/K/V ~ N(0,1) rounded to bf16, logits ~ sigma * N(0,1) in fp32.
 from .configs import CONFIGS, GRConfig, get_config
 from .generate import (
     bf16_bits_to_f32,
+    e4m3_bits_to_f32,
     f32_to_bf16_bits,
+    f32_to_e4m3_bits,
     initial_beam_state,
     make_attention_inputs,
     make_item_table,
@@ -24,7 +26,7 @@ from .generate import (
 )
 
 __all__ = [
-    "CONFIGS", "GRConfig", "get_config", "bf16_bits_to_f32", "f32_to_bf16_bits",
+    "CONFIGS", "GRConfig", "get_config", "bf16_bits_to_f32", "f32_to_bf16_bits", "e4m3_bits_to_f32", "f32_to_e4m3_bits",
     "initial_beam_state", "make_attention_inputs", "make_item_table", "make_logits",
     "make_prompt_lengths", "rng_for",
 ]

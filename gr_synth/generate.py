@@ -26,6 +26,29 @@ def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
     return (np.ascontiguousarray(b, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
 
 
+def e4m3_bits_to_f32(b: np.ndarray) -> np.ndarray:
+    """Decode OCP FP8 E4M3 (1 sign, 4 exponent bits with bias 7, 3 mantissa bits; no infinities, 0x7f / 0xff = NaN)."""
+    codes = np.arange(256, dtype=np.uint32)
+    sign = np.where(codes & 0x80, -1.0, 1.0)
+    e = ((codes >> 3) & 0xF).astype(np.int32)
+    m = (codes & 0x7).astype(np.float64)
+    val = np.where(e == 0, m / 8.0 * 2.0 ** -6, (1.0 + m / 8.0) * 2.0 ** (e - 7).astype(np.float64))
+    val = np.where((codes & 0x7F) == 0x7F, np.nan, val) * sign
+    return val.astype(np.float32)[np.ascontiguousarray(b, dtype=np.uint8)]
+
+
+def f32_to_e4m3_bits(x: np.ndarray) -> np.ndarray:
+    """Round fp32 to OCP FP8 E4M3 (round-to-nearest-even on the representable grid, saturating at +-448)."""
+    grid = e4m3_bits_to_f32(np.arange(0, 0x7F, dtype=np.uint8)).astype(np.float64)      # the 127 non-negative finite values, ascending
+    a = np.minimum(np.abs(np.ascontiguousarray(x, dtype=np.float32)).astype(np.float64), 448.0)
+    hi = np.clip(np.searchsorted(grid, a, side="left"), 1, len(grid) - 1)
+    lo = hi - 1
+    d_lo, d_hi = a - grid[lo], grid[hi] - a
+    pick_hi = (d_hi < d_lo) | ((d_hi == d_lo) & (hi % 2 == 0))                          # ties go to the even code
+    code = np.where(pick_hi, hi, lo).astype(np.uint8)
+    return np.where(np.signbit(x), code | np.uint8(0x80), code).astype(np.uint8)
+
+
 def _randn_bf16(rng: np.random.Generator, shape) -> np.ndarray:
     n = int(np.prod(shape))
     out = np.empty(n, dtype=np.uint16)

@@ -73,6 +73,34 @@ def attn_unified(q, k_shared, v_shared, cu_seqlens, k_unshared, v_unshared, u, s
     return out, lse
 
 
+def attn_unified_f32kv(q, k_shared_f32, v_shared_f32, cu_seqlens, k_unshared, v_unshared, u, sm_scale, triples=None):
+    """Unified-cache attention with the prompt K/V given as fp32 values (a narrower storage format, already widened).
+
+    q, k_unshared, v_unshared: bf16 bit patterns as in attn_unified; k_shared_f32 / v_shared_f32: float32 [total_L,Hkv,d].
+    Returns (out fp64 [n,d], lse fp64 [n]).
+    """
+    lib = _load()
+    B, W, Hq, d = q.shape
+    Hkv = k_shared_f32.shape[1]
+    ND = k_unshared.shape[2]
+    if triples is None:
+        bb, ww, hh = np.meshgrid(np.arange(B), np.arange(W), np.arange(Hq), indexing="ij")
+        triples = np.stack([bb.ravel(), ww.ravel(), hh.ravel()], axis=1)
+    triples = np.ascontiguousarray(triples, dtype=np.int32)
+    n = triples.shape[0]
+    out = np.empty((n, d), dtype=np.float64)
+    lse = np.empty(n, dtype=np.float64)
+    rc = lib.oracle_attn_unified_f32kv(
+        ctypes.c_int(B), ctypes.c_int(W), ctypes.c_int(Hq), ctypes.c_int(Hkv), ctypes.c_int(d), ctypes.c_int(ND),
+        ctypes.c_int(int(u)), ctypes.c_float(float(sm_scale)),
+        _p(q, np.uint16), _p(k_shared_f32, np.float32), _p(v_shared_f32, np.float32), _p(cu_seqlens, np.int32),
+        _p(k_unshared, np.uint16), _p(v_unshared, np.uint16), _p(triples, np.int32), ctypes.c_int64(n),
+        _p(out, np.float64), _p(lse, np.float64))
+    if rc != 0:
+        raise RuntimeError(f"oracle_attn_unified_f32kv failed: {rc}")
+    return out, lse
+
+
 def prefill_attn_causal(q, k, v, cu_seqlens, sm_scale, triples=None):
     """Causal self-attention over packed prompts.  bf16 tensors are uint16 bit patterns.
 

@@ -102,6 +102,66 @@ int oracle_attn_unified(int B, int W, int Hq, int Hkv, int d, int ND, int u, flo
 }
 
 /* ------------------------------------------------------------------------------------------------
+ * The same unified-cache attention with the prompt K/V given as fp32 values (Section 5.1's shared cache held in
+ * a narrower storage format and widened before use: the caller passes the widened values, e.g. FP8 codes times
+ * their scale).  Everything else as in oracle_attn_unified: the beam's own decode tokens stay bf16, the beam's
+ * sequence is its private copy [prompt ; own tokens], one softmax over all of it, fp64 accumulation.
+ *
+ * k_sh, v_sh   fp32 [total_L, Hkv, d]
+ * ------------------------------------------------------------------------------------------------ */
+int oracle_attn_unified_f32kv(int B, int W, int Hq, int Hkv, int d, int ND, int u, float sm_scale,
+                              const uint16_t *q, const float *k_sh, const float *v_sh,
+                              const int32_t *cu_seqlens, const uint16_t *k_un, const uint16_t *v_un,
+                              const int32_t *triples, int64_t n, double *out, double *lse_out) {
+    if (B <= 0 || W <= 0 || Hq <= 0 || Hkv <= 0 || d <= 0 || Hq % Hkv != 0 || u < 0 || u > ND)
+        return ORACLE_ERR_ARG;
+    const int g = Hq / Hkv;
+    int status = ORACLE_OK;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t t = 0; t < n; t++) {
+        const int b = triples[3 * t], w = triples[3 * t + 1], hq = triples[3 * t + 2];
+        if (b < 0 || b >= B || w < 0 || w >= W || hq < 0 || hq >= Hq) { status = ORACLE_ERR_ARG; continue; }
+        const int hk = hq / g;
+        const int64_t row0 = cu_seqlens[b];
+        const int64_t L = (int64_t)cu_seqlens[b + 1] - row0;
+        const int64_t n_uni = L + u;
+        double *K_uni = (double *)malloc(sizeof(double) * (size_t)(n_uni > 0 ? n_uni : 1) * d);
+        double *V_uni = (double *)malloc(sizeof(double) * (size_t)(n_uni > 0 ? n_uni : 1) * d);
+        double *s = (double *)malloc(sizeof(double) * (size_t)(n_uni > 0 ? n_uni : 1));
+        if (!K_uni || !V_uni || !s) { status = ORACLE_ERR_MEM; free(K_uni); free(V_uni); free(s); continue; }
+        for (int64_t j = 0; j < L; j++)
+            for (int c = 0; c < d; c++) {
+                K_uni[j * d + c] = (double)k_sh[((row0 + j) * Hkv + hk) * d + c];
+                V_uni[j * d + c] = (double)v_sh[((row0 + j) * Hkv + hk) * d + c];
+            }
+        for (int j = 0; j < u; j++)
+            for (int c = 0; c < d; c++) {
+                const int64_t src = ((((int64_t)b * W + w) * ND + j) * Hkv + hk) * d + c;
+                K_uni[(L + j) * d + c] = (double)bf16_bits_to_float(k_un[src]);
+                V_uni[(L + j) * d + c] = (double)bf16_bits_to_float(v_un[src]);
+            }
+        const uint16_t *qrow = q + (((int64_t)b * W + w) * Hq + hq) * d;
+        double smax = -INFINITY;
+        for (int64_t j = 0; j < n_uni; j++) {
+            double acc = 0.0;
+            for (int c = 0; c < d; c++) acc += (double)bf16_bits_to_float(qrow[c]) * K_uni[j * d + c];
+            s[j] = (double)sm_scale * acc;
+            if (s[j] > smax) smax = s[j];
+        }
+        double denom = 0.0;
+        for (int64_t j = 0; j < n_uni; j++) { s[j] = exp(s[j] - smax); denom += s[j]; }
+        for (int c = 0; c < d; c++) {
+            double acc = 0.0;
+            for (int64_t j = 0; j < n_uni; j++) acc += s[j] * V_uni[j * d + c];
+            out[t * d + c] = (n_uni > 0) ? acc / denom : 0.0;
+        }
+        if (lse_out) lse_out[t] = (n_uni > 0) ? smax + log(denom) : -INFINITY;
+        free(K_uni); free(V_uni); free(s);
+    }
+    return status;
+}
+
+/* ------------------------------------------------------------------------------------------------
  * Causal self-attention over the prompt (the prefill phase that fills the shared cache: Section 2.2.1
  * "Prefill", Section 5.1; the abstract's claim that prefill and decode go through one staged computation).
  * The textbook definition, one query row at a time: token i of request b, query head hq (KV head hq / g),

@@ -164,3 +164,58 @@ def test_invariants(oracle_lib):
     g = Hq // c["k_shared"].shape[1]
     np.testing.assert_array_equal(out5.reshape(B, W, Hq, d)[:, :, :g], out.reshape(B, W, Hq, d)[:, :, :g])
     assert not np.array_equal(out5.reshape(B, W, Hq, d)[:, :, g:], out.reshape(B, W, Hq, d)[:, :, g:])
+
+
+# ---- the variant that takes the prompt K/V as fp32 values (narrow storage formats widened by the caller) -------------
+def test_f32kv_variant_equals_the_bf16_routine_on_bf16_values(oracle_lib):
+    """bf16 values are fp32 values: on them the two routines must agree to the last bit of their fp64 arithmetic."""
+    c = _rand_case(21, u=2)
+    ref, ref_lse = _run(oracle_lib, c, 0.375)
+    got, got_lse = oracle_lib.attn_unified_f32kv(c["q"], bf16_bits_to_f32(c["k_shared"]), bf16_bits_to_f32(c["v_shared"]), c["cu_seqlens"],
+                                                 c["k_unshared"], c["v_unshared"], c["u"], 0.375)
+    np.testing.assert_array_equal(got, ref)
+    np.testing.assert_array_equal(got_lse, ref_lse)
+
+
+def test_f32kv_variant_matches_torch_sdpa_with_scaled_fp8_values(oracle_lib):
+    """FP8 codes times per-tensor scales as the prompt cache, bf16 own tokens: torch's library attention in fp64 on the
+    concatenated sequence; and linearity in the V scale (doubling it doubles the prompt's share of the output)."""
+    c = _rand_case(22, B=2, W=3, Hq=4, Hkv=2, d=16, u=1, lens=(9, 14))
+    k_scale, v_scale = np.float32(0.4375), np.float32(1.75)
+    k8 = gr_synth.e4m3_bits_to_f32(gr_synth.f32_to_e4m3_bits(bf16_bits_to_f32(c["k_shared"]) / k_scale)) * k_scale
+    v8 = gr_synth.e4m3_bits_to_f32(gr_synth.f32_to_e4m3_bits(bf16_bits_to_f32(c["v_shared"]) / v_scale)) * v_scale
+    scale = 0.25
+    out, lse = oracle_lib.attn_unified_f32kv(c["q"], k8, v8, c["cu_seqlens"], c["k_unshared"], c["v_unshared"], c["u"], scale)
+    B, W, Hq, d = c["q"].shape
+    g = Hq // 2
+    out = out.reshape(B, W, Hq, d)
+    q = torch.from_numpy(bf16_bits_to_f32(c["q"]).astype(np.float64))
+    ku = torch.from_numpy(bf16_bits_to_f32(c["k_unshared"]).astype(np.float64))
+    vu = torch.from_numpy(bf16_bits_to_f32(c["v_unshared"]).astype(np.float64))
+    ks, vs = torch.from_numpy(k8.astype(np.float64)), torch.from_numpy(v8.astype(np.float64))
+    for b in range(B):
+        lo, hi = int(c["cu_seqlens"][b]), int(c["cu_seqlens"][b + 1])
+        for w in range(W):
+            k = torch.cat([ks[lo:hi], ku[b, w, :1]], 0).repeat_interleave(g, dim=1)
+            v = torch.cat([vs[lo:hi], vu[b, w, :1]], 0).repeat_interleave(g, dim=1)
+            ref = torch.nn.functional.scaled_dot_product_attention(q[b, w][None, :, None, :], k.permute(1, 0, 2)[None], v.permute(1, 0, 2)[None], scale=scale)
+            np.testing.assert_allclose(out[b, w], ref[0, :, 0, :].numpy(), rtol=0, atol=1e-12)
+    # with no own tokens the output is linear in the prompt V values
+    o1, _ = oracle_lib.attn_unified_f32kv(c["q"], k8, v8, c["cu_seqlens"], c["k_unshared"], c["v_unshared"], 0, scale)
+    o2, _ = oracle_lib.attn_unified_f32kv(c["q"], k8, (2 * v8).astype(np.float32), c["cu_seqlens"], c["k_unshared"], c["v_unshared"], 0, scale)
+    np.testing.assert_allclose(o2, 2 * o1, rtol=1e-15, atol=0)
+
+
+def test_e4m3_helpers_match_torch(oracle_lib):
+    """The FP8 E4M3 encode / decode used to build such inputs, against torch's float8_e4m3fn."""
+    codes = np.arange(256, dtype=np.uint8)
+    mine = gr_synth.e4m3_bits_to_f32(codes)
+    ref = torch.from_numpy(codes).view(torch.float8_e4m3fn).float().numpy()
+    ok = ~np.isnan(ref)
+    np.testing.assert_array_equal(mine[ok], ref[ok])
+    assert np.isnan(mine[~ok]).all() and (~ok).sum() == 2
+    rng = np.random.default_rng(0)
+    x = (rng.standard_normal(100000) * rng.choice([1e-3, 0.1, 1, 10, 100], 100000)).astype(np.float32)
+    x = x[np.abs(x) <= 448]
+    np.testing.assert_array_equal(gr_synth.f32_to_e4m3_bits(x), torch.from_numpy(x).to(torch.float8_e4m3fn).view(torch.uint8).numpy())
+    np.testing.assert_array_equal(gr_synth.f32_to_e4m3_bits(np.array([1e9, -1e9], dtype=np.float32)), [0x7E, 0xFE])      # saturates
