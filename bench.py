@@ -321,7 +321,7 @@ def main():
             sel_by_level[f"level{s}"] = dict(ms=round(float(np.mean(ms)), 4), live_rows=live_rows[s])
 
     # ---------------- extras, outside the headline's timed region
-    roofline_select, reorder, graph, streams, peaks, prefill, layers = None, None, None, None, None, None, None
+    roofline_select, reorder, graph, streams, peaks, prefill, layers, fp8kv = None, None, None, None, None, None, None, None
     if not args.no_extras:
         # (0) the item step on its dense paths: every live row streamed in full (GR_SELECT_FORCE_DENSE, and mask = NULL),
         # on the levels where all B*W rows are live.  Algorithmic bytes = live rows x (4V logits + V/8 mask bits); the time
@@ -451,6 +451,28 @@ def main():
             del qp, op
         except Exception as e:
             prefill = dict(error=f"{type(e).__name__}: {e}"[:300])
+        # (4b) the same attention over a prompt cache stored as FP8 E4M3 codes (one scale per tensor)
+        try:
+            def to_fp8(t):
+                scale = float(t.float().abs().max().item()) / 448.0
+                codes = torch.empty(t.shape, dtype=torch.uint8, device=dev)
+                step_rows = 1 << 16
+                for r0 in range(0, t.shape[0], step_rows):      # in slices: the fp32 intermediate of the whole cache is large
+                    codes[r0:r0 + step_rows] = (t[r0:r0 + step_rows].float() / scale).to(torch.float8_e4m3fn).view(torch.uint8)
+                return codes, scale
+            k8, k_scale = to_fp8(k_sh)
+            v8, v_scale = to_fp8(v_sh)
+            a3 = attn_in[ND - 1]
+            run8 = lambda: gr.gr_beam_attn_fp8kv(a3["q"], k8, v8, k_scale, v_scale, d_cu, a3["ku"], a3["vu"], a3["u"], scale, max_L, total_L,
+                                                 out=buf["out"], workspace=buf["ws_attn"])
+            for _ in range(5):
+                run8()
+            ms = _elapsed(torch, run8, 10)
+            fp8kv = dict(ms=round(ms, 4), TFLOPs=round(flops[ND - 1] / (ms * 1e-3) / 1e12, 1), bf16_cache_ms=round(float(np.mean([attn_ms[i] for i in range(K) if i % ND == ND - 1] or [0])), 4),
+                         note="u = 3 launch; codes widened to bf16 on the way into LDS, bf16 MFMA as before; the cache is half the bytes")
+            del k8, v8
+        except Exception as e:
+            fp8kv = dict(error=f"{type(e).__name__}: {e}"[:300])
         # (5) a per-layer loop: n_layers attention calls (each layer its own K/V and Q) + one item step per decode step,
         # the three levels captured as one graph.  Layer count is a stand-in (no model geometry is given); what it shows
         # is that the step scales by the attention time per layer with nothing added between the calls.
@@ -525,7 +547,7 @@ def main():
         roofline=roofline, roofline_select=roofline_select, cpu_baseline=cpu,
         attn=dict(ms_by_u={f"u{s + 1}": round(float(np.mean([attn_ms[i] for i in range(K) if i % ND == s] or [0])), 4) for s in range(ND)},
                   tflops=round(attn_tflops, 2), ms_first20_after_idle=round(cold_ms, 4)),
-        select=sel_by_level, reorder=reorder, graph=graph, two_streams=streams, prefill=prefill, layers=layers, peaks_measured=peaks,
+        select=sel_by_level, reorder=reorder, graph=graph, two_streams=streams, prefill=prefill, fp8kv=fp8kv, layers=layers, peaks_measured=peaks,
         prewarm=dict(ms=args.prewarm_ms, steps=prewarm_steps), wall_s=round(wall, 3), input_gen_s=round(t_gen, 1))
     print(json.dumps(line))
 

@@ -86,6 +86,22 @@ size_t gr_beam_attn_workspace_bytes(const gr_attn_params* p);
 gr_status gr_beam_attn(const gr_attn_params* p, void* workspace, size_t workspace_bytes, void* stream);
 
 /* ------------------------------------------------------------------------------------------------
+ * gr_beam_attn_fp8kv - gr_beam_attn over a shared (prompt) cache stored in FP8: the "separated KV cache" of
+ * Section 5.1 with its large, read-only half held at one byte per element.  `attn.k_shared` / `attn.v_shared` point
+ * to OCP FP8 E4M3 codes, uint8 [total_L, Hkv, d]; the value of an element is code * k_scale (resp. * v_scale),
+ * one positive finite scale per tensor.  Everything else (Q, the beams' own decode-token caches, output, workspace,
+ * launch rule, errors) is as for gr_beam_attn; the codes are widened to bf16 exactly on their way into LDS and the
+ * scales are applied to the scores and to the prompt's share of the output in fp32.
+ * ------------------------------------------------------------------------------------------------ */
+typedef struct {
+  gr_attn_params attn;        /* as for gr_beam_attn, except the element type of k_shared / v_shared */
+  float k_scale, v_scale;     /* value = code * scale; must be positive and finite                    */
+} gr_attn_fp8kv_params;
+
+/* Workspace: gr_beam_attn_workspace_bytes(&p->attn). */
+gr_status gr_beam_attn_fp8kv(const gr_attn_fp8kv_params* p, void* workspace, size_t workspace_bytes, void* stream);
+
+/* ------------------------------------------------------------------------------------------------
  * gr_prefill_attn - causal self-attention over the packed prompts: the prefill phase that produces the
  * shared cache (Section 2.2.1 "Prefill"; Section 5.1: the shared cache stores the prompt's token-level
  * outputs of the prefill phase; the abstract's single staged computation for prefill and decode).

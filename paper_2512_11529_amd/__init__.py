@@ -16,7 +16,7 @@ import os
 
 from . import build as _build
 
-__all__ = ["load_library", "gr_beam_attn", "gr_prefill_attn", "gr_item_mask_build", "gr_beam_select", "gr_beam_select_noalloc", "gr_beam_reorder",
+__all__ = ["load_library", "gr_beam_attn", "gr_beam_attn_fp8kv", "gr_prefill_attn", "gr_item_mask_build", "gr_beam_select", "gr_beam_select_noalloc", "gr_beam_reorder",
            "gr_status_string",
            "attn_workspace_bytes", "select_workspace_bytes", "GrError", "GR_SELECT_FORCE_DENSE", "LIB_PATH",
            "gr_diag_stream_read", "gr_diag_mfma_loop", "gr_diag_attn_plan", "gr_diag_issue_loop"]
@@ -39,6 +39,10 @@ class _AttnParams(ctypes.Structure):
                 ("q", ctypes.c_void_p), ("k_shared", ctypes.c_void_p), ("v_shared", ctypes.c_void_p),
                 ("cu_seqlens", ctypes.c_void_p), ("k_unshared", ctypes.c_void_p), ("v_unshared", ctypes.c_void_p),
                 ("out", ctypes.c_void_p), ("lse_out", ctypes.c_void_p)]
+
+
+class _AttnFp8Params(ctypes.Structure):
+    _fields_ = [("attn", _AttnParams), ("k_scale", ctypes.c_float), ("v_scale", ctypes.c_float)]
 
 
 class _PrefillParams(ctypes.Structure):
@@ -91,6 +95,8 @@ def load_library(path: str = None):
     lib.gr_diag_stream_read.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_void_p]
     lib.gr_diag_mfma_loop.restype = ctypes.c_int32
     lib.gr_diag_mfma_loop.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p]
+    lib.gr_beam_attn_fp8kv.restype = ctypes.c_int32
+    lib.gr_beam_attn_fp8kv.argtypes = [ctypes.POINTER(_AttnFp8Params), ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
     lib.gr_prefill_attn.restype = ctypes.c_int32
     lib.gr_prefill_attn.argtypes = [ctypes.POINTER(_PrefillParams), ctypes.c_void_p]
     lib.gr_diag_issue_loop.restype = ctypes.c_int32
@@ -180,6 +186,38 @@ def gr_beam_attn(q, k_shared, v_shared, cu_seqlens, k_unshared, v_unshared, u, s
     rc = lib.gr_beam_attn(ctypes.byref(p), _ptr(workspace), ws_bytes, _stream(stream))
     if rc != 0:
         raise GrError(rc, "gr_beam_attn")
+    return out, lse_out
+
+
+def gr_beam_attn_fp8kv(q, k_shared_fp8, v_shared_fp8, k_scale, v_scale, cu_seqlens, k_unshared, v_unshared, u, sm_scale, max_L, total_L,
+                       out=None, lse_out=None, workspace=None, stream=None):
+    """gr_beam_attn over a prompt cache stored as FP8 E4M3 codes: k/v_shared_fp8 uint8 CUDA tensors [total_L,Hkv,d],
+    value = code * scale.  Everything else as for gr_beam_attn."""
+    import torch
+    lib = load_library()
+    B, W, Hq, d = q.shape
+    _check(q, torch.bfloat16, None, "q")
+    _check(k_shared_fp8, torch.uint8, (k_shared_fp8.shape[0], k_shared_fp8.shape[1], d), "k_shared_fp8")
+    _check(v_shared_fp8, torch.uint8, tuple(k_shared_fp8.shape), "v_shared_fp8")
+    _check(cu_seqlens, torch.int32, (B + 1,), "cu_seqlens")
+    _check(k_unshared, torch.bfloat16, (B, W, k_unshared.shape[2], k_shared_fp8.shape[1], d), "k_unshared")
+    _check(v_unshared, torch.bfloat16, tuple(k_unshared.shape), "v_unshared")
+    if k_shared_fp8.shape[0] < int(total_L):
+        raise ValueError("k_shared_fp8 has fewer rows than total_L")
+    if out is None:
+        out = torch.empty_like(q)
+    _check(out, torch.bfloat16, tuple(q.shape), "out")
+    if lse_out is not None:
+        _check(lse_out, torch.float32, (B, W, Hq), "lse_out")
+    p = _AttnFp8Params(_attn_params(q, k_shared_fp8, v_shared_fp8, cu_seqlens, k_unshared, v_unshared, u, sm_scale, max_L, total_L, out, lse_out),
+                       float(k_scale), float(v_scale))
+    need = int(lib.gr_beam_attn_workspace_bytes(ctypes.byref(p.attn)))
+    if workspace is None and need > 0:
+        workspace = _scratch(need, q.device, stream)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    rc = lib.gr_beam_attn_fp8kv(ctypes.byref(p), _ptr(workspace), ws_bytes, _stream(stream))
+    if rc != 0:
+        raise GrError(rc, "gr_beam_attn_fp8kv")
     return out, lse_out
 
 

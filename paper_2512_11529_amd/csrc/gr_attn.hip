@@ -34,6 +34,7 @@ struct AttnCtx {
   int nsplit;       // L segments per request
   int n_groups;     // B * Hkv * nsplit
   float c;          // sm_scale * log2(e)
+  float k_scale, v_scale;   // FP8 prompt cache: value = code * scale (1 for the bf16 cache)
   const uint16_t* q;
   const uint16_t* ks;
   const uint16_t* vs;
@@ -287,7 +288,12 @@ struct AttnTile {
 // its own tokens (row r = token r / g, head r % g of the KV group), a row block only walks the K/V tiles up to its
 // last token, scores of keys after a row's token are set to -inf on the tiles that straddle the diagonal, and there
 // is no own-token stage and no L split.
-template <int D, int NCB, int NWAVES, bool CAUSAL>
+// KV8 = true: the prompt K/V are FP8 E4M3 codes with one scale per tensor (value = code * scale).  The tiles are widened
+// to bf16 (exactly) on their way into LDS: 8-byte loads into registers one tile ahead, four conversions per 16-byte piece,
+// a ds_write into the same swizzled layout the direct loads fill.  The scales never touch the tiles: the K scale goes into
+// the exponent scale of the prompt loop, and at the end of the loop the running maximum (x k_scale) and O (x v_scale) are
+// put into true units, which is where the bf16 own-token stage and the epilogue work.
+template <int D, int NCB, int NWAVES, bool CAUSAL, bool KV8>
 __global__ void __launch_bounds__(NWAVES * 64) __attribute__((amdgpu_waves_per_eu(NCB == 1 ? 2 : 1, NCB == 1 ? 2 : 1)))
 k_beam_attn(AttnCtx c) {
   using T = AttnTile<D, NCB>;
@@ -383,9 +389,11 @@ k_beam_attn(AttnCtx c) {
   // (V) make irrelevant.  The loads are issued from inline assembly so that the compiler, which cannot tell the
   // tile buffers apart, does not make every later LDS read wait for them; `tiles_landed` waits for all of this
   // wave's loads, and the barrier that follows publishes every wave's.
-  const uint32_t tok_bytes = (uint32_t)c.Hkv * D * 2;       // bytes between consecutive tokens
-  const char* kbase = (const char*)c.ks + ((size_t)row0 * c.Hkv + kvh) * D * 2;
-  const char* vbase = (const char*)c.vs + ((size_t)row0 * c.Hkv + kvh) * D * 2;
+  constexpr int EB = KV8 ? 1 : 2;                            // bytes per stored K/V element
+  const uint32_t tok_bytes = (uint32_t)c.Hkv * D * EB;      // bytes between consecutive tokens
+  const char* kbase = (const char*)c.ks + ((size_t)row0 * c.Hkv + kvh) * D * EB;
+  const char* vbase = (const char*)c.vs + ((size_t)row0 * c.Hkv + kvh) * D * EB;
+  const float cp = KV8 ? c.c * c.k_scale : c.c;              // exponent scale of the prompt loop
   const typename T::Rd rdo = T::make_rd(lane);
   const int wave_u = __builtin_amdgcn_readfirstlane(wave);
   int crow[CPW];                                             // this lane's row inside a tile, per chunk
@@ -419,7 +427,37 @@ k_beam_attn(AttnCtx c) {
       }
     }
   };
-  auto tiles_landed = [&]() { __builtin_amdgcn_s_waitcnt(0x0F70); };     // vmcnt(0)
+  auto tiles_landed = [&]() { if (!KV8) __builtin_amdgcn_s_waitcnt(0x0F70); };     // vmcnt(0)
+  // FP8 tiles: piece p = tid + i * NT of a tile = 8 codes of row p / PPR; registers one tile ahead
+  constexpr int P8 = KT * PPR / NT;                          // pieces per thread and tile
+  struct Stage8 { uint2 r[P8]; };
+  auto gload8 = [&](bool is_k, int t) {
+    const int tok0 = seg0 + t * KT;
+    const char* tile = (is_k ? kbase : vbase) + (size_t)tok0 * tok_bytes;
+    const int nvalid = seg1 - tok0;                          // >= 1; rows past the end re-read the last valid row
+    Stage8 st;
+#pragma unroll
+    for (int i = 0; i < P8; i++) {
+      const int p = tid + i * NT, row = min(p / PPR, nvalid - 1), col = p % PPR;
+      st.r[i] = *(const uint2*)(tile + (size_t)row * tok_bytes + col * 8);
+    }
+    return st;
+  };
+  auto lstore8 = [&](uint16_t* dst, bool is_k, const Stage8& st) {
+#pragma unroll
+    for (int i = 0; i < P8; i++) {
+      const int p = tid + i * NT, row = p / PPR, slot = (p % PPR) ^ (is_k ? T::swz_k(row) : T::swz_v(row));
+      const bf16x2 e01 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8((int)st.r[i].x, 1.0f, false);
+      const bf16x2 e23 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8((int)st.r[i].x, 1.0f, true);
+      const bf16x2 e45 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8((int)st.r[i].y, 1.0f, false);
+      const bf16x2 e67 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8((int)st.r[i].y, 1.0f, true);
+      uint4 v;
+      v.x = __builtin_bit_cast(uint32_t, e01); v.y = __builtin_bit_cast(uint32_t, e23);
+      v.z = __builtin_bit_cast(uint32_t, e45); v.w = __builtin_bit_cast(uint32_t, e67);
+      *(uint4*)(dst + row * D + slot * 8) = v;
+    }
+  };
+  Stage8 k8, v8;
 
   // ---- geometry of the unshared stage (segment 0 only): every beam's own u decode tokens go through
   // the same MFMA path as the prompt.  The 32 query columns of a wave belong to a handful of beams
@@ -472,7 +510,10 @@ k_beam_attn(AttnCtx c) {
   };
 
   // first prompt tiles: requested before anything waits on memory (when Q has its own LDS region)
-  if (kQSeparate && ntiles > 0) {
+  Stage8 k8b;
+  if (KV8) {
+    if (ntiles > 0) { k8 = gload8(true, 0); v8 = gload8(false, 0); k8b = gload8(true, min(1, ntiles - 1)); }
+  } else if (kQSeparate && ntiles > 0) {
     tload(true, 0, 0); tload(false, 0, 0);
     tload(true, 1, min(1, ntiles - 1));
   }
@@ -489,10 +530,15 @@ k_beam_attn(AttnCtx c) {
     for (int ks = 0; ks < D / 16; ks++) qop[0][ks] = as_bf16x8(*(const uint4*)(&s_q[(wave * 32 + n32) * KSTR + ks * 16 + G * 8]));
     if (!kQSeparate) {
       __syncthreads();                               // the tile slots may now be overwritten
-      if (ntiles > 0) {
+      if (!KV8 && ntiles > 0) {
         tload(true, 0, 0); tload(false, 0, 0);
         tload(true, 1, min(1, ntiles - 1));
       }
+    }
+    if (KV8 && ntiles > 0) {
+      lstore8(s_k, true, k8); lstore8(s_v, false, v8); lstore8(s_k + TILE, true, k8b);
+      k8 = gload8(true, min(2, ntiles - 1));
+      v8 = gload8(false, min(1, ntiles - 1));
     }
   }
 
@@ -533,9 +579,9 @@ k_beam_attn(AttnCtx c) {
         causal_mask(s_in, seg0 + t * KT);
         mx_cur = T::colmax(s_in);
       }
-      if (__any(mx_cur * c.c > m_run[0] * c.c + T::kLazy)) {
+      if (__any(mx_cur * cp > m_run[0] * cp + T::kLazy)) {
         const float m_new = fmaxf(m_run[0], mx_cur);
-        const float alpha = __builtin_amdgcn_exp2f((m_run[0] - m_new) * c.c);
+        const float alpha = __builtin_amdgcn_exp2f((m_run[0] - m_new) * cp);
 #pragma unroll
         for (int db = 0; db < D / 32; db++)
 #pragma unroll
@@ -545,9 +591,16 @@ k_beam_attn(AttnCtx c) {
       }
       tiles_landed();                                               // this wave's K(t+1) and V(t) loads (issued one step ago)
       __syncthreads();                                              // everyone's; and everyone is done with K(t) and V(t-1)
-      tload(true, t & 1, min(t + 2, tl));                           // K(t+2) over K(t)
-      tload(false, (t + 1) & 1, min(t + 1, tl));                    // V(t+1) over V(t-1)
-      T::fused(s_k + ((t + 1) & 1) * TILE, s_v + (t & 1) * TILE, qop, s_in, s_out, o_acc, m_run[0] * c.c, c.c, l_run[0], mx_cur, rdo);
+      if (KV8) {
+        lstore8(s_k + (t & 1) * TILE, true, k8);                    // K(t+2) over K(t)
+        lstore8(s_v + ((t + 1) & 1) * TILE, false, v8);             // V(t+1) over V(t-1)
+        k8 = gload8(true, min(t + 3, tl));
+        v8 = gload8(false, min(t + 2, tl));
+      } else {
+        tload(true, t & 1, min(t + 2, tl));                         // K(t+2) over K(t)
+        tload(false, (t + 1) & 1, min(t + 1, tl));                  // V(t+1) over V(t-1)
+      }
+      T::fused(s_k + ((t + 1) & 1) * TILE, s_v + (t & 1) * TILE, qop, s_in, s_out, o_acc, m_run[0] * cp, cp, l_run[0], mx_cur, rdo);
     };
     // the last tile of the segment: the only one that can be partial, and it has no successor
     auto last = [&](f32x16 (&s_in)[KT / 32][NCB], int t) {
@@ -569,7 +622,7 @@ k_beam_attn(AttnCtx c) {
       bf16x8 pop[KT / 16][NCB];
       float alpha[NCB];
       bool upd[NCB];
-      T::softmax(s_in, pop, m_run, l_run, alpha, upd, c.c);
+      T::softmax(s_in, pop, m_run, l_run, alpha, upd, cp);
       rescale(alpha, upd);
       T::pv(s_v + (t & 1) * TILE, pop, o_acc, rdo);
     };
@@ -593,6 +646,13 @@ k_beam_attn(AttnCtx c) {
       step(s_b, s_a, t + 1);
     }
     last(s_a, t);
+    if (KV8) {                                         // prompt loop -> true units
+      m_run[0] *= c.k_scale;
+#pragma unroll
+      for (int db = 0; db < D / 32; db++)
+#pragma unroll
+        for (int i = 0; i < 16; i++) o_acc[db][0][i] *= c.v_scale;
+    }
   }
 
   // ---- unshared stage (segment 0): every beam's own u decode tokens, through the same MFMA path.
@@ -874,9 +934,11 @@ extern "C" size_t gr_beam_attn_workspace_bytes(const gr_attn_params* p) {
   return need;
 }
 
-extern "C" gr_status gr_beam_attn(const gr_attn_params* p, void* workspace, size_t workspace_bytes, void* stream_) {
+namespace {
+gr_status attn_run(const gr_attn_params* p, bool kv8, float k_scale, float v_scale, void* workspace, size_t workspace_bytes, void* stream_) {
   hipStream_t stream = (hipStream_t)stream_;
   if (!p) return GR_ERR_INVALID_ARG;
+  if (kv8 && (!(k_scale > 0.f) || !(k_scale < INFINITY) || !(v_scale > 0.f) || !(v_scale < INFINITY))) return GR_ERR_INVALID_ARG;
   if (p->B <= 0 || p->W <= 0 || p->Hq <= 0 || p->Hkv <= 0 || p->d <= 0 || p->ND < 0 || p->u < 0 || p->u > p->ND)
     return GR_ERR_INVALID_ARG;
   if (p->max_L < 0 || p->total_L < 0 || p->total_L > (int64_t)p->max_L * p->B) return GR_ERR_INVALID_ARG;
@@ -904,6 +966,7 @@ extern "C" gr_status gr_beam_attn(const gr_attn_params* p, void* workspace, size
   c.nsplit = plan.nsplit;
   c.n_groups = p->B * p->Hkv * c.nsplit;
   c.c = p->sm_scale * kLog2e;
+  c.k_scale = kv8 ? k_scale : 1.f; c.v_scale = kv8 ? v_scale : 1.f;
   c.q = (const uint16_t*)p->q; c.ks = (const uint16_t*)p->k_shared; c.vs = (const uint16_t*)p->v_shared;
   c.cu = p->cu_seqlens; c.ku = (const uint16_t*)p->k_unshared; c.vu = (const uint16_t*)p->v_unshared;
   c.out = (uint16_t*)p->out; c.lse = p->lse_out;
@@ -930,8 +993,13 @@ extern "C" gr_status gr_beam_attn(const gr_attn_params* p, void* workspace, size
   const size_t lds = attn_lds_bytes(p->d, plan.mwg);
 #define GR_LAUNCH_ATTN(DD, NCB_, NW_)                                                                                        \
   do {                                                                                                                       \
-    GR_HIP_TRY(hipFuncSetAttribute((const void*)k_beam_attn<DD, NCB_, NW_, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)); \
-    hipLaunchKernelGGL((k_beam_attn<DD, NCB_, NW_, false>), dim3((unsigned)grid), dim3(NW_ * 64), lds, stream, c);           \
+    if (kv8) {                                                                                                               \
+      GR_HIP_TRY(hipFuncSetAttribute((const void*)k_beam_attn<DD, NCB_, NW_, false, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)); \
+      hipLaunchKernelGGL((k_beam_attn<DD, NCB_, NW_, false, true>), dim3((unsigned)grid), dim3(NW_ * 64), lds, stream, c);   \
+    } else {                                                                                                                 \
+      GR_HIP_TRY(hipFuncSetAttribute((const void*)k_beam_attn<DD, NCB_, NW_, false, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)); \
+      hipLaunchKernelGGL((k_beam_attn<DD, NCB_, NW_, false, false>), dim3((unsigned)grid), dim3(NW_ * 64), lds, stream, c);  \
+    }                                                                                                                        \
   } while (0)
   if (p->d == 128) {
     if (plan.mwg == 256) GR_LAUNCH_ATTN(128, 1, 8); else GR_LAUNCH_ATTN(128, 1, 4);
@@ -947,6 +1015,17 @@ extern "C" gr_status gr_beam_attn(const gr_attn_params* p, void* workspace, size
   }
   GR_HIP_TRY(hipGetLastError());
   return GR_OK;
+}
+}  // namespace
+
+extern "C" gr_status gr_beam_attn(const gr_attn_params* p, void* workspace, size_t workspace_bytes, void* stream) {
+  return attn_run(p, false, 1.f, 1.f, workspace, workspace_bytes, stream);
+}
+
+// The same attention over a prompt cache stored as FP8 E4M3 codes with one scale per tensor.
+extern "C" gr_status gr_beam_attn_fp8kv(const gr_attn_fp8kv_params* p, void* workspace, size_t workspace_bytes, void* stream) {
+  if (!p) return GR_ERR_INVALID_ARG;
+  return attn_run(&p->attn, true, p->k_scale, p->v_scale, workspace, workspace_bytes, stream);
 }
 
 // Causal prompt attention through the same kernel (CAUSAL = true).
@@ -977,6 +1056,7 @@ extern "C" gr_status gr_prefill_attn(const gr_prefill_params* p, void* stream_) 
   c.nsplit = 1;
   c.n_groups = p->B * p->Hkv;
   c.c = p->sm_scale * kLog2e;
+  c.k_scale = 1.f; c.v_scale = 1.f;
   c.q = (const uint16_t*)p->q; c.ks = (const uint16_t*)p->k; c.vs = (const uint16_t*)p->v;
   c.cu = p->cu_seqlens; c.ku = nullptr; c.vu = nullptr;
   c.out = (uint16_t*)p->out; c.lse = p->lse_out;
@@ -987,8 +1067,8 @@ extern "C" gr_status gr_prefill_attn(const gr_prefill_params* p, void* stream_) 
   const size_t lds = attn_lds_bytes(p->d, mwg);
 #define GR_LAUNCH_PREFILL(DD, NW_)                                                                                              \
   do {                                                                                                                         \
-    GR_HIP_TRY(hipFuncSetAttribute((const void*)k_beam_attn<DD, 1, NW_, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)); \
-    hipLaunchKernelGGL((k_beam_attn<DD, 1, NW_, true>), dim3((unsigned)grid), dim3(NW_ * 64), lds, stream, c);                 \
+    GR_HIP_TRY(hipFuncSetAttribute((const void*)k_beam_attn<DD, 1, NW_, true, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)); \
+    hipLaunchKernelGGL((k_beam_attn<DD, 1, NW_, true, false>), dim3((unsigned)grid), dim3(NW_ * 64), lds, stream, c);          \
   } while (0)
   if (p->d == 128) {
     if (mwg == 256) GR_LAUNCH_PREFILL(128, 8); else GR_LAUNCH_PREFILL(128, 4);
