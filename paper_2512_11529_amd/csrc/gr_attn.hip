@@ -431,15 +431,23 @@ k_beam_attn(AttnCtx c) {
   // FP8 tiles: piece p = tid + i * NT of a tile = 8 codes of row p / PPR; registers one tile ahead
   constexpr int P8 = KT * PPR / NT;                          // pieces per thread and tile
   struct Stage8 { uint2 r[P8]; };
+  uint32_t off8[P8];                                         // byte offsets of this thread's pieces inside a full tile
+#pragma unroll
+  for (int i = 0; i < P8; i++) { const int p = tid + i * NT; off8[i] = (uint32_t)(p / PPR) * tok_bytes + (uint32_t)(p % PPR) * 8; }
   auto gload8 = [&](bool is_k, int t) {
     const int tok0 = seg0 + t * KT;
     const char* tile = (is_k ? kbase : vbase) + (size_t)tok0 * tok_bytes;
     const int nvalid = seg1 - tok0;                          // >= 1; rows past the end re-read the last valid row
     Stage8 st;
+    if (nvalid >= KT) {
 #pragma unroll
-    for (int i = 0; i < P8; i++) {
-      const int p = tid + i * NT, row = min(p / PPR, nvalid - 1), col = p % PPR;
-      st.r[i] = *(const uint2*)(tile + (size_t)row * tok_bytes + col * 8);
+      for (int i = 0; i < P8; i++) st.r[i] = *(const uint2*)(tile + off8[i]);
+    } else {
+#pragma unroll
+      for (int i = 0; i < P8; i++) {
+        const int p = tid + i * NT, row = min(p / PPR, nvalid - 1), col = p % PPR;
+        st.r[i] = *(const uint2*)(tile + (size_t)row * tok_bytes + col * 8);
+      }
     }
     return st;
   };
