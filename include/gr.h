@@ -8,13 +8,18 @@
  *      and the best W of the W*V candidates (Sections 6.1, 6.2), in fixed caller-owned buffers
  *      (Section 6.3);
  *   3. the move of every surviving beam's own decode cache to its new slot, in place (Section 5.1).
+ * Beside the step: the prefill that fills the shared cache (gr_prefill_attn), the step's attention over a shared
+ * cache stored in FP8 (gr_beam_attn_fp8kv), an item step for callers that cannot allocate
+ * (gr_beam_select_noalloc), and a few diagnostics used by the benchmark (gr_diag_*).
  *
  * Conventions for every entry point
  *   - All data pointers are DEVICE pointers unless a comment says "host".  Parameter structs and
  *     scalar arguments are host values read before the call returns.
  *   - The caller owns every buffer, including workspaces and the mask blob.  The library never
- *     allocates, frees or keeps device memory and holds no state between calls.
- *   - gr_beam_attn and gr_beam_select only enqueue kernels on `stream` (a hipStream_t passed as
+ *     allocates, frees or keeps device memory and holds no state between calls (two exceptions, stated
+ *     where they are declared: the static scratch array of gr_beam_select_noalloc and the launch-plan
+ *     override of gr_diag_attn_plan).
+ *   - The attention calls, gr_beam_select and gr_beam_reorder only enqueue kernels on `stream` (a hipStream_t passed as
  *     void*, NULL = default stream); they never synchronise.  gr_item_mask_build is a load-time
  *     call and synchronises `stream` once to report table errors.
  *   - Return value: GR_OK or a negative gr_status.  Nothing is printed, thrown or aborted.
