@@ -250,6 +250,8 @@ __device__ __forceinline__ void row_dense(const SelCtx& c, int owns_dead, int ro
   int par = 0;
   const int tid = threadIdx.x;
   const float s_in = c.scores_in[row];
+  // (the first token of the prefix picks the level-1 mask row: asked for together with the score)
+  const int t1 = (c.blob && c.step == 1) ? c.prefix_in[(size_t)row * c.depth] : -1;
   if (!(s_in > -INFINITY)) {
     if (owns_dead && tid == 0) { c.row_mode[row] = ROW_DEAD; c.row_bias[row] = -INFINITY; c.row_top[row] = -INFINITY; }
     return;                                        // the keys of a dead row are never read
@@ -270,31 +272,50 @@ __device__ __forceinline__ void row_dense(const SelCtx& c, int owns_dead, int ro
     }
   };
   const bool surely_streamed = !c.blob || c.step == 0 || (c.flags & GR_SELECT_FORCE_DENSE);
-  if (reg && surely_streamed) request_row();
   const int32_t* list = nullptr;
-  int n_list = 0;
+  int n_list = 0;                                  // number of valid children, where it is looked up
   MaskView mv;
   mv.ok = true;
+  const int words = (V + 31) >> 5;
+  // the dense mask row of this beam (levels 0 and 1), or nothing (no mask, last level, mismatched blob); a row that
+  // is streamed whatever its child count asks for the mask words and the logits at once
+  const uint32_t* mrow = nullptr;
+  uint32_t mw[kRegV4];
+#pragma unroll
+  for (int i = 0; i < kRegV4; i++) mw[i] = 0u;
   if (c.blob) {
     mv = mask_view(c.blob, c.V, c.depth);
-    if (c.step >= 1) {
+    if (mv.ok) {
+      if (c.step == 0) mrow = mv.l0;
+      else if (c.step == 1 && t1 >= 0 && t1 < V) mrow = mv.l1 + (size_t)t1 * mv.words;
+    }
+    auto request_mask = [&]() {
+#pragma unroll
+      for (int i = 0; i < kRegV4; i++) {
+        const int wi = (tid >> 3) + 32 * i;        // float4 p = tid + i * kRowThreads has its nibble in word p >> 3
+        if (wi < words) mw[i] = mrow[wi];
+      }
+    };
+    if (reg && surely_streamed) {
+      if (mrow) request_mask();
+      request_row();
+    }
+    // a level-1 row that is streamed whatever its child count needs no look-up: its mask row says what is valid
+    if (c.step >= 1 && !(c.step == 1 && (c.flags & GR_SELECT_FORCE_DENSE))) {
       row_children(c, mv, row, &list, &n_list);
       if (row_is_sparse(c, n_list)) return;      // a gathered row: rows_sparse owns it
     }
-  }
-  if (reg && !surely_streamed) request_row();
+    if (reg && !surely_streamed) {
+      request_row();
+      if (mrow) request_mask();
+    }
+  } else if (reg) request_row();
+  // validity bits from the mask words: bit 4 i + j <-> token 4 (tid + i * kRowThreads) + j
+  uint32_t mbits = 0;
+#pragma unroll
+  for (int i = 0; i < kRegV4; i++) mbits |= ((mw[i] >> (4 * (tid & 7))) & 0xfu) << (4 * i);
   if (tid < 64) s_tab[tid] = c_exp_tab[tid];
   const ExpK ek = exp_consts();
-  const int words = (V + 31) >> 5;
-  // the dense mask row of this beam (levels 0 and 1), or nothing (no mask, last level, mismatched blob)
-  const uint32_t* mrow = nullptr;
-  if (c.blob && mv.ok) {
-    if (c.step == 0) mrow = mv.l0;
-    else if (c.step == 1) {
-      const int t1 = c.prefix_in[(size_t)row * c.depth];
-      if (t1 >= 0 && t1 < V) mrow = mv.l1 + (size_t)t1 * mv.words;
-    }
-  }
   // the last level has no dense mask: a long child list is set position by position in an empty LDS mask
   // (Section 6.1's sparse form applied to an existing mask); a short one is matched against directly below
   const bool lds_mask = !reg || (c.blob && c.step == 2 && n_list > 64);
@@ -334,14 +355,7 @@ __device__ __forceinline__ void row_dense(const SelCtx& c, int owns_dead, int ro
           if (((t >> 2) & (kRowThreads - 1)) == tid) vbits |= 1u << (4 * (t >> 10) + (t & 3));
         }
       } else if (mrow) {
-        uint32_t mw[kRegV4];
-#pragma unroll
-        for (int i = 0; i < kRegV4; i++) {
-          const int wi = (tid >> 3) + 32 * i;      // float4 p = tid + i * kRowThreads has its nibble in word p >> 3
-          mw[i] = (wi < words) ? mrow[wi] : 0u;
-        }
-#pragma unroll
-        for (int i = 0; i < kRegV4; i++) vbits |= ((mw[i] >> (4 * (tid & 7))) & 0xfu) << (4 * i);
+        vbits = mbits;
       }
 #pragma unroll
       for (int i = 0; i < kRegV4; i++) {
@@ -357,11 +371,16 @@ __device__ __forceinline__ void row_dense(const SelCtx& c, int owns_dead, int ro
     if (m > -INFINITY) {
       const double rc = -(double)m * ek.c;
       const float lo = m - 600.f;
-      if (c.blob && c.step >= 1 && n_list <= kQueueMax) {
-        // thinly populated row: the valid logits are packed into a queue (thread order, so the sum is
-        // reproducible) and exponentiated with full lanes
-        uint32_t total;
-        uint32_t pos = block_excl_scan<NW>((uint32_t)__popc(vbits), &total, s_redu, par);
+      // thinly populated row: the valid logits are packed into a queue (thread order, so the sum is
+      // reproducible) and exponentiated with full lanes.  The count of valid bits decides (it equals the child
+      // count where that was looked up; a row known to be well populated skips the count).
+      bool queued = c.blob && c.step >= 1 && n_list <= kQueueMax;
+      uint32_t total = 0, pos = 0;
+      if (queued) {
+        pos = block_excl_scan<NW>((uint32_t)__popc(vbits), &total, s_redu, par);
+        queued = total <= (uint32_t)kQueueMax;
+      }
+      if (queued) {
 #pragma unroll
         for (int i = 0; i < kRegV4; i++) {
           if (((vbits >> (4 * i)) & 1u) && pos < (uint32_t)kQueueMax) s_q[pos++] = xr[i].x;
