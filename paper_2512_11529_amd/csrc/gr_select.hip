@@ -35,7 +35,7 @@ constexpr int kHistBins = 2048;
 constexpr int kMaxMaskWords = 1024; // V <= 32768
 constexpr int kRegV4 = 8;           // float4 per thread kept in registers (V <= 8192)
 constexpr int kMaxW = 2048;
-constexpr size_t kSelLdsBytes = (size_t)kListCap * 8 + (size_t)kHistBins * 4 + (size_t)kChunkCap * 4 + (size_t)kMaxW * 16;
+constexpr size_t kSelLdsBytes = (size_t)kListCap * 8 + (size_t)kHistBins * 4 + (size_t)kChunkCap * 4 + (size_t)kMaxW * 20;
 
 enum { ROW_DEAD = 0, ROW_DENSE = 1, ROW_SPARSE = 2 };
 
@@ -660,7 +660,8 @@ __global__ void __launch_bounds__(kSelThreads) k_select(SelCtx c) {
   float* s_rbias = (float*)(s_chunks + kChunkCap);          // per beam row of the request: bias,
   int32_t* s_rmode = (int32_t*)(s_rbias + kMaxW);            // mode,
   int32_t* s_ra = s_rmode + kMaxW;                           // first token (step 1) or table range start (step 2),
-  int32_t* s_rb = s_ra + kMaxW;                              // table range end (step 2)
+  int32_t* s_rb = s_ra + kMaxW;                              // start of the child list (step 1) or table range end (step 2),
+  int32_t* s_rc = s_rb + kMaxW;                              // end of the child list (step 1)
   __shared__ float s_redf[kSelThreads / 64];
   __shared__ uint32_t s_redu[2 * (kSelThreads / 64)];
   __shared__ uint16_t s_live[kMaxW];
@@ -679,22 +680,34 @@ __global__ void __launch_bounds__(kSelThreads) k_select(SelCtx c) {
   float hi = -INFINITY;
   for (int w = tid; w < c.W; w += kSelThreads) {
     const size_t row = (size_t)b * c.W + w;
+    // (everything a row can need is asked for at once; what a dead row returns is ignored)
     const int mode = c.row_mode[row];
+    const float bias = c.row_bias[row], top = c.row_top[row];
+    int a = 0, bb = 0, cc = 0;
+    if (c.blob && c.step == 1) {
+      a = c.prefix_in[row * c.depth];
+    } else if (c.blob && c.step == 2) {
+      a = c.range_in[2 * row]; bb = c.range_in[2 * row + 1];
+    }
     s_rmode[w] = mode;
-    s_rbias[w] = c.row_bias[row];
-    int a = 0, bb = 0;
+    s_rbias[w] = bias;
     if (mode != ROW_DEAD) {
-      hi = fmaxf(hi, c.row_top[row]);
+      hi = fmaxf(hi, top);
       s_live[atomicAdd(&s_nlive, 1u)] = (uint16_t)w;
       if (c.blob && c.step == 1) {
-        a = c.prefix_in[row * c.depth];
+        // the row's child list, looked up once here for the re-read of gathered chunks and for the output
+        const bool ok = mv.ok && a >= 0 && a < c.V;
+        bb = ok ? mv.pair_off[a] : 0;
+        cc = ok ? mv.pair_off[a + 1] : 0;
       } else if (c.blob && c.step == 2) {
-        a = c.range_in[2 * row]; bb = c.range_in[2 * row + 1];
-        if (a < 0 || bb < a || (int64_t)bb > mv.n_items) { a = 0; bb = 0; }
+        if (!mv.ok || a < 0 || bb < a || (int64_t)bb > mv.n_items) { a = 0; bb = 0; }
       }
+    } else {
+      a = 0; bb = 0;
     }
     s_ra[w] = a;
     s_rb[w] = bb;
+    s_rc[w] = cc;
   }
   hi = block_max2<NW>(hi, s_redf);         // (has the barriers that publish the row table)
   const int nlive = (int)s_nlive;
@@ -816,12 +829,8 @@ __global__ void __launch_bounds__(kSelThreads) k_select(SelCtx c) {
               // gathered row: chunk k = children k, k + 64, ...
               const int32_t* list;
               int nlist;
-              if (c.step == 1) {
-                const int t1 = s_ra[w];
-                const bool ok = t1 >= 0 && t1 < c.V;
-                const int p0 = ok ? mv.pair_off[t1] : 0, p1 = ok ? mv.pair_off[t1 + 1] : 0;
-                list = mv.pair_t2 + p0; nlist = p1 - p0;
-              } else { list = mv.t3 + s_ra[w]; nlist = s_rb[w] - s_ra[w]; }
+              if (c.step == 1) { list = mv.pair_t2 + s_rb[w]; nlist = s_rc[w] - s_rb[w]; }
+              else { list = mv.t3 + s_ra[w]; nlist = s_rb[w] - s_ra[w]; }
               const int i = k + kSparseKeys * e;
               if (k < kSparseKeys && e < kSparseMax / kSparseKeys && i < nlist) {
                 const int t = list[i];
@@ -969,14 +978,12 @@ __global__ void __launch_bounds__(kSelThreads) k_select(SelCtx c) {
         if (c.step == 0) {
           r_lo = mv.off1[token]; r_hi = mv.off1[token + 1];
         } else if (c.step == 1) {
-          const int32_t* list; int nl;
-          row_children(c, mv, (int)prow, &list, &nl);
-          const int p = (int)(list - mv.pair_t2) + lower_bound_i32(list, nl, token);
+          const int p0 = s_rb[parent];                       // (the parent's child list, from the row table)
+          const int p = p0 + lower_bound_i32(mv.pair_t2 + p0, s_rc[parent] - p0, token);
           r_lo = mv.pair_row[p]; r_hi = mv.pair_row[p + 1];
         } else {
-          const int32_t* list; int nl;
-          row_children(c, mv, (int)prow, &list, &nl);
-          r_lo = (int)(list - mv.t3) + lower_bound_i32(list, nl, token);
+          const int lo = s_ra[parent];
+          r_lo = lo + lower_bound_i32(mv.t3 + lo, s_rb[parent] - lo, token);
           r_hi = r_lo + 1;
           item = r_lo;
         }
