@@ -792,21 +792,20 @@ __global__ void __launch_bounds__(kSelThreads) k_select(SelCtx c) {
     if (nc > kChunkCap) {
       need_fallback = true;
     } else {
-      // ---- re-read only those chunks; keep their candidates that reach the threshold.  Four
-      // (chunk, element) slots per thread and round, all of their loads issued before any is used.
+      // ---- re-read only those chunks; keep their candidates that reach the threshold.  Twelve (chunk, element)
+      // slots per thread and round, all of their loads issued before any is used: the usual W-odd chunks of 32
+      // elements fit in one round.  bits: 0 = not a candidate, 1 = valid, 2 = valid if in the row's child list.
       const int epc = max(c.epc, kSparseMax / kSparseKeys);
       const int total = nc * epc;
-      constexpr int U = 8;
+      constexpr int U = 12;
       for (int base = 0; base < total; base += U * kSelThreads) {
         int wv[U], tok[U];
         float x[U];
         uint32_t bits[U];
-        const int32_t* lst[U];
-        int nl[U];
 #pragma unroll
         for (int q = 0; q < U; q++) {
           const int idx = base + q * kSelThreads + tid;
-          tok[q] = -1; x[q] = 0.f; bits[q] = 0; lst[q] = nullptr; nl[q] = 0; wv[q] = 0;
+          tok[q] = -1; x[q] = 0.f; bits[q] = 0; wv[q] = 0;
           if (idx < total) {
             const uint32_t ent = s_chunks[idx / epc];
             const int e = idx % epc;
@@ -823,7 +822,7 @@ __global__ void __launch_bounds__(kSelThreads) k_select(SelCtx c) {
                 else if (c.step == 1) {
                   const int t1 = s_ra[w];
                   bits[q] = (t1 >= 0 && t1 < c.V) ? ((mv.l1[(size_t)t1 * mv.words + (t >> 5)] >> (t & 31)) & 1u) : 0u;
-                } else { lst[q] = mv.t3 + s_ra[w]; nl[q] = s_rb[w] - s_ra[w]; }
+                } else bits[q] = 2u;
               }
             } else {
               // gathered row: chunk k = children k, k + 64, ...
@@ -843,13 +842,12 @@ __global__ void __launch_bounds__(kSelThreads) k_select(SelCtx c) {
         }
 #pragma unroll
         for (int q = 0; q < U; q++) {
-          if (tok[q] < 0) continue;
-          bool ok = bits[q] != 0;
-          if (lst[q]) {                     // last level, streamed row: membership in the row's short child list
-            const int pos = lower_bound_i32(lst[q], nl[q], tok[q]);
-            ok = pos < nl[q] && lst[q][pos] == tok[q];
+          if (tok[q] < 0 || bits[q] == 0) continue;
+          if (bits[q] == 2u) {              // last level, streamed row: membership in the row's short child list
+            const int lo = s_ra[wv[q]], nl = s_rb[wv[q]] - lo;
+            const int pos = lower_bound_i32(mv.t3 + lo, nl, tok[q]);
+            if (!(pos < nl && mv.t3[lo + pos] == tok[q])) continue;
           }
-          if (!ok) continue;
           const float score = __fadd_rn(s_rbias[wv[q]], x[q]);
           if (key_bin(hi, score) <= thr) {
             const uint32_t pos = atomicAdd(&s_n, 1u);
