@@ -91,14 +91,15 @@ def summarize_trace(path):
         print(f"{name:12s} " + "   ".join(f"level{lvl} {sum(acc[(lvl, name)]) / max(len(acc[(lvl, name)]), 1) / 1e3:7.1f} us" for lvl in range(3)))
 
 
-def issue_test(torch, gr, dev):
+def issue_test(torch, gr, dev, sigma=0.01):
     """How much vector work hides behind matrix instructions on one SIMD: time per slot of { MFMA, n FMA, m exp } per wave,
     for two and four waves per SIMD (nanoseconds per slot and SIMD; the MFMA-only row is the matrix pipe's own rate)."""
     sink = torch.zeros(4, dtype=torch.float32, device=dev)
-    ops = (torch.randn(8192, dtype=torch.float32, device=dev) * 0.01).to(torch.bfloat16)
+    ops = (torch.randn(8192, dtype=torch.float32, device=dev) * sigma).to(torch.bfloat16)
     iters = 2048
     combos = [(1, 0, 0), (1, 2, 0), (1, 4, 0), (1, 8, 0), (1, 12, 0), (1, 0, 1), (1, 2, 1), (1, 3, 1), (1, 4, 1), (1, 4, 2),
               (0, 4, 0), (0, 12, 0), (0, 0, 1), (0, 0, 4), (0, 4, 1)]
+    print(f"operands N(0, {sigma}^2) bf16")
     print("mfma n_fma n_exp | ns per slot and SIMD: 2 waves/SIMD  4 waves/SIMD")
     for mf, nv, nx in combos:
         cells = []
@@ -110,6 +111,22 @@ def issue_test(torch, gr, dev):
             slots = wgs * 8 / 1024 * iters * 4
             cells.append(f"{ms * 1e6 / slots:6.1f}")
         print(f"{mf:4d} {nv:5d} {nx:5d} | {cells[0]}  {cells[1]}", flush=True)
+    # the MFMA's first operand from LDS (one conflict-free ds_read_b128 per wave and read), as in the attention loop
+    print("with the MFMA's A operand read from LDS every k-th slot (0 = from registers); two waves per SIMD")
+    print("n_fma n_exp | every 0   every 2   every 1")
+    rounds = 680
+    for nv, nx, evs in ((0, 0, (0, 2, 1)), (3, 1, (0, 2, 1)), (5, 0, (0, None, 1)), (0, 2, (0, None, 1))):
+        cells = []
+        for ev in evs:
+            if ev is None:
+                cells.append("     -")
+                continue
+            run = lambda: gr.gr_diag_issue_loop_lds(ops, 256, rounds, nv, nx, ev, sink)
+            for _ in range(3):
+                run()
+            ms = _elapsed(torch, run, 5)
+            cells.append(f"{ms * 1e6 / (256 * 8 / 1024 * rounds * 12):6.1f}")
+        print(f"{nv:5d} {nx:5d} | " + "    ".join(cells), flush=True)
 
 
 def sweep_attn_plan(torch, gr, dev):
@@ -176,6 +193,7 @@ def main():
     ap.add_argument("--layers", type=int, default=4, help="attention calls per decode step in the per-layer extra leg")
     ap.add_argument("--sweep-attn-plan", action="store_true", help="print the launch-plan sweep table and exit")
     ap.add_argument("--issue-test", action="store_true", help="print the MFMA / VALU issue test table and exit")
+    ap.add_argument("--issue-sigma", type=float, default=0.01, help="standard deviation of the issue test's MFMA operands")
     ap.add_argument("--summarize-trace", metavar="CSV", help="per-level kernel means from a rocprofv3 kernel-trace CSV of this benchmark "
                                                               "(made with --kernel-trace --output-format csv ... --no-extras), then exit; needs no GPU")
     args = ap.parse_args()
@@ -203,7 +221,7 @@ def main():
         sweep_attn_plan(torch, gr, dev)
         return
     if args.issue_test:
-        issue_test(torch, gr, dev)
+        issue_test(torch, gr, dev, args.issue_sigma)
         return
     cfg = gr_synth.get_config(args.config)
     B, W, V, ND, Hq, Hkv, d = cfg.B, cfg.W, cfg.V, cfg.ND, cfg.Hq, cfg.Hkv, cfg.d

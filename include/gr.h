@@ -266,10 +266,16 @@ gr_status gr_beam_reorder(int32_t B, int32_t W, int32_t ND, int32_t Hkv, int32_t
  *   `with_mfma`, `n_fma` independent fp32 FMAs, `n_exp` v_exp_f32 }.  Built combinations (n_fma, n_exp): (0,0) (2,0)
  *   (4,0) (8,0) (12,0) (0,1) (2,1) (3,1) (4,1) (4,2) (0,4); others return UNSUPPORTED.  Operands and sink as for
  *   gr_diag_mfma_loop.
+ * gr_diag_issue_loop_lds: the same test with the MFMA's first operand coming from LDS, as the attention loop's K and V
+ *   operands do: `rounds` x 12 slots per wavefront; every `lds_every`-th slot (0 = never, 1, 2) uses an operand that a
+ *   conflict-free ds_read_b128 fetched three slots earlier.  Built (n_fma, n_exp, lds_every): (0,0,*) (3,1,*) (5,0,0)
+ *   (5,0,1) (0,2,0) (0,2,1).  Uses 64 KiB of LDS per workgroup.
  * Errors: INVALID_ARG, UNSUPPORTED, HIP.
  * ------------------------------------------------------------------------------------------------ */
 gr_status gr_diag_issue_loop(const void* operands, int32_t workgroups, int32_t iters, int32_t n_fma, int32_t n_exp,
                              int32_t with_mfma, void* sink, void* stream);
+gr_status gr_diag_issue_loop_lds(const void* operands, int32_t workgroups, int32_t rounds, int32_t n_fma, int32_t n_exp,
+                                 int32_t lds_every, void* sink, void* stream);
 gr_status gr_diag_attn_plan(int32_t rows_per_workgroup, int32_t l_segments);
 gr_status gr_diag_stream_read(const void* src, size_t bytes, void* sink, void* stream);
 gr_status gr_diag_mfma_loop(const void* operands, int32_t workgroups, int32_t iters, void* sink, void* stream);

@@ -19,7 +19,7 @@ from . import build as _build
 __all__ = ["load_library", "gr_beam_attn", "gr_beam_attn_fp8kv", "gr_prefill_attn", "gr_item_mask_build", "gr_beam_select", "gr_beam_select_noalloc", "gr_beam_reorder",
            "gr_status_string",
            "attn_workspace_bytes", "select_workspace_bytes", "GrError", "GR_SELECT_FORCE_DENSE", "LIB_PATH",
-           "gr_diag_stream_read", "gr_diag_mfma_loop", "gr_diag_attn_plan", "gr_diag_issue_loop"]
+           "gr_diag_stream_read", "gr_diag_mfma_loop", "gr_diag_attn_plan", "gr_diag_issue_loop", "gr_diag_issue_loop_lds"]
 
 LIB_PATH = _build.LIB_PATH
 GR_SELECT_FORCE_DENSE = 1
@@ -101,6 +101,8 @@ def load_library(path: str = None):
     lib.gr_prefill_attn.argtypes = [ctypes.POINTER(_PrefillParams), ctypes.c_void_p]
     lib.gr_diag_issue_loop.restype = ctypes.c_int32
     lib.gr_diag_issue_loop.argtypes = [ctypes.c_void_p] + [ctypes.c_int32] * 5 + [ctypes.c_void_p] * 2
+    lib.gr_diag_issue_loop_lds.restype = ctypes.c_int32
+    lib.gr_diag_issue_loop_lds.argtypes = [ctypes.c_void_p] + [ctypes.c_int32] * 5 + [ctypes.c_void_p] * 2
     lib.gr_diag_attn_plan.restype = ctypes.c_int32
     lib.gr_diag_attn_plan.argtypes = [ctypes.c_int32, ctypes.c_int32]
     lib.gr_diag_mfma_flops.restype = ctypes.c_double
@@ -362,6 +364,16 @@ def gr_diag_issue_loop(operands, workgroups, iters, n_fma, n_exp, with_mfma, sin
                                            _ptr(sink), _stream(stream))
     if rc != 0:
         raise GrError(rc, "gr_diag_issue_loop")
+
+
+def gr_diag_issue_loop_lds(operands, workgroups, rounds, n_fma, n_exp, lds_every, sink, stream=None):
+    """Enqueue the issue test with the MFMA's first operand read from LDS every `lds_every`-th slot (see gr.h)."""
+    if operands.numel() * operands.element_size() < 16384:
+        raise ValueError("operands must hold 16 KiB")
+    rc = load_library().gr_diag_issue_loop_lds(_ptr(operands), int(workgroups), int(rounds), int(n_fma), int(n_exp), int(lds_every),
+                                               _ptr(sink), _stream(stream))
+    if rc != 0:
+        raise GrError(rc, "gr_diag_issue_loop_lds")
 
 
 def gr_diag_stream_read(src, sink, stream=None):
