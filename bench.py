@@ -427,6 +427,31 @@ def main():
             gms2 = _elapsed(torch, g2.replay, cycles) / ND
             graph["with_reorder"] = dict(graph_ms_per_step=round(gms2, 4), graph_steps_per_s=round(1000.0 / gms2, 3),
                                          eager_ms_per_step=round(eager2, 4), eager_steps_per_s=round(1000.0 / eager2, 3))
+            # and with a slot table that follows the beams instead of moving their rows (attn_slots -> select -> slot update)
+            slots = [torch.empty((B, W, ND), dtype=torch.int32, device=dev) for _ in range(2)]
+            ident_parent = torch.zeros((B, W), dtype=torch.int32, device=dev)
+
+            def slot_cycle():
+                gr.gr_beam_slot_update(ident_parent, None, 0, ND, out=slots[0])
+                for s in range(ND):
+                    a = attn_in[s]
+                    gr.gr_beam_attn_slots(a["q"], k_sh, v_sh, d_cu, ku_g[s], vu_g[s], slots[s & 1], a["u"], scale, max_L, total_L,
+                                          out=buf["out"], workspace=buf["ws_attn"])
+                    select(s)
+                    gr.gr_beam_slot_update(buf["sel_out"][s]["parent"], slots[s & 1], s + 1, ND, out=slots[(s + 1) & 1])
+            for _ in range(3):
+                slot_cycle()
+            torch.cuda.synchronize()
+            g3 = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g3):
+                slot_cycle()
+            for _ in range(3):
+                g3.replay()
+            torch.cuda.synchronize()
+            gms3 = _elapsed(torch, g3.replay, cycles) / ND
+            graph["with_slots"] = dict(graph_ms_per_step=round(gms3, 4), graph_steps_per_s=round(1000.0 / gms3, 3),
+                                       note="no cache bytes move: gr_beam_attn_slots reads each beam's rows through the table "
+                                            "that gr_beam_slot_update maintains")
             del ku_g, vu_g
         except Exception as e:          # the headline above stands on its own
             graph = dict(error=f"{type(e).__name__}: {e}"[:300])

@@ -7,7 +7,8 @@
  *   2. the beam item step: valid-item mask, log-softmax over valid tokens, cumulative beam score,
  *      and the best W of the W*V candidates (Sections 6.1, 6.2), in fixed caller-owned buffers
  *      (Section 6.3);
- *   3. the move of every surviving beam's own decode cache to its new slot, in place (Section 5.1).
+ *   3. the move of every surviving beam's own decode cache to its new slot, in place (Section 5.1) - or, moving no
+ *      bytes, the update of a slot table that the attention follows (gr_beam_slot_update, gr_beam_attn_slots).
  * Beside the step: the prefill that fills the shared cache (gr_prefill_attn), the step's attention over a shared
  * cache stored in FP8 (gr_beam_attn_fp8kv), an item step for callers that cannot allocate
  * (gr_beam_select_noalloc), and a few diagnostics used by the benchmark (gr_diag_*).
@@ -246,6 +247,31 @@ gr_status gr_beam_select_noalloc(const gr_select_params* p, void* stream);
  * ------------------------------------------------------------------------------------------------ */
 gr_status gr_beam_reorder(int32_t B, int32_t W, int32_t ND, int32_t Hkv, int32_t d, int32_t u,
                           const int32_t* parent, void* k_unshared, void* v_unshared, void* stream);
+
+/* ------------------------------------------------------------------------------------------------
+ * gr_beam_slot_update / gr_beam_attn_slots - the same hand-over of the unshared cache between decode steps
+ * (Section 5.1) without moving any cache bytes.
+ *
+ * The paper moves each surviving beam's rows to its new place.  Here the rows stay where they were written and a
+ * slot table follows the beams instead: token t of beam w of request b is read from row slot[b, w, t] of that
+ * request's [W * ND] rows of k_unshared / v_unshared (the same [B, W, ND, Hkv, d] buffers, seen as B blocks of
+ * W * ND rows).  A row is written once - the caller writes the K/V of beam j's token t to row j * ND + t, as for
+ * gr_beam_attn - and never overwritten afterwards, because position t only ever receives tokens of step t.
+ *
+ * gr_beam_slot_update: slot_out[b, j, t] = slot_in[b, parent[b, j], t] for t < u (the tokens the new beam shares
+ *   with its parent); = j * ND + t for t >= u (its own rows, where the next tokens go) and for every t of a dead
+ *   slot (parent outside [0, W)).  slot_in == NULL means the identity table (before the first beam step).  parent:
+ *   device int32 [B, W]; slot_in, slot_out: device int32 [B, W, ND], distinct.  u = tokens per beam before the
+ *   step that produced `parent`, 0 <= u <= ND.
+ * gr_beam_attn_slots: gr_beam_attn with `slot` (device int32 [B, W, ND], required) applied to every read of
+ *   k_unshared / v_unshared; an entry outside [0, W * ND) is read as the identity entry instead of being followed.
+ *   Same parameters, workspace, launch rule and results as gr_beam_attn on a cache reordered by gr_beam_reorder
+ *   (bit for bit for live beams).
+ * Both only enqueue on `stream`.  Errors: INVALID_ARG, UNSUPPORTED, WORKSPACE_TOO_SMALL, HIP.
+ * ------------------------------------------------------------------------------------------------ */
+gr_status gr_beam_slot_update(int32_t B, int32_t W, int32_t ND, int32_t u, const int32_t* parent, const int32_t* slot_in,
+                              int32_t* slot_out, void* stream);
+gr_status gr_beam_attn_slots(const gr_attn_params* p, const int32_t* slot, void* workspace, size_t workspace_bytes, void* stream);
 
 /* ------------------------------------------------------------------------------------------------
  * Diagnostics: the rates this GPU really sustains, reported by the benchmark next to the datasheet peaks

@@ -19,7 +19,7 @@ from . import build as _build
 __all__ = ["load_library", "gr_beam_attn", "gr_beam_attn_fp8kv", "gr_prefill_attn", "gr_item_mask_build", "gr_beam_select", "gr_beam_select_noalloc", "gr_beam_reorder",
            "gr_status_string",
            "attn_workspace_bytes", "select_workspace_bytes", "GrError", "GR_SELECT_FORCE_DENSE", "LIB_PATH",
-           "gr_diag_stream_read", "gr_diag_mfma_loop", "gr_diag_attn_plan", "gr_diag_issue_loop", "gr_diag_issue_loop_lds"]
+           "gr_diag_stream_read", "gr_diag_mfma_loop", "gr_diag_attn_plan", "gr_diag_issue_loop", "gr_diag_issue_loop_lds", "gr_beam_attn_slots", "gr_beam_slot_update"]
 
 LIB_PATH = _build.LIB_PATH
 GR_SELECT_FORCE_DENSE = 1
@@ -101,6 +101,10 @@ def load_library(path: str = None):
     lib.gr_prefill_attn.argtypes = [ctypes.POINTER(_PrefillParams), ctypes.c_void_p]
     lib.gr_diag_issue_loop.restype = ctypes.c_int32
     lib.gr_diag_issue_loop.argtypes = [ctypes.c_void_p] + [ctypes.c_int32] * 5 + [ctypes.c_void_p] * 2
+    lib.gr_beam_attn_slots.restype = ctypes.c_int32
+    lib.gr_beam_attn_slots.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+    lib.gr_beam_slot_update.restype = ctypes.c_int32
+    lib.gr_beam_slot_update.argtypes = [ctypes.c_int32] * 4 + [ctypes.c_void_p] * 4
     lib.gr_diag_issue_loop_lds.restype = ctypes.c_int32
     lib.gr_diag_issue_loop_lds.argtypes = [ctypes.c_void_p] + [ctypes.c_int32] * 5 + [ctypes.c_void_p] * 2
     lib.gr_diag_attn_plan.restype = ctypes.c_int32
@@ -160,9 +164,10 @@ def attn_workspace_bytes(B, W, Hq, Hkv, d, max_L, total_L=None) -> int:
 
 
 def gr_beam_attn(q, k_shared, v_shared, cu_seqlens, k_unshared, v_unshared, u, sm_scale, max_L, total_L,
-                 out=None, lse_out=None, workspace=None, stream=None):
+                 out=None, lse_out=None, workspace=None, stream=None, slot=None):
     """Shared-prefix beam attention.  bf16 CUDA tensors: q [B,W,Hq,d], k/v_shared [total_L,Hkv,d],
     k/v_unshared [B,W,ND,Hkv,d]; cu_seqlens int32 [B+1].  max_L / total_L are host integers.
+    `slot` (int32 [B,W,ND], optional) routes the call to gr_beam_attn_slots: the own-token rows are read through it.
     Returns (out bf16 [B,W,Hq,d], lse fp32 [B,W,Hq] or None).  Enqueues on `stream` (default: current)."""
     import torch
     lib = load_library()
@@ -185,10 +190,23 @@ def gr_beam_attn(q, k_shared, v_shared, cu_seqlens, k_unshared, v_unshared, u, s
     if workspace is None and need > 0:
         workspace = _scratch(need, q.device, stream)
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
-    rc = lib.gr_beam_attn(ctypes.byref(p), _ptr(workspace), ws_bytes, _stream(stream))
+    if slot is not None:
+        _check(slot, torch.int32, (B, W, k_unshared.shape[2]), "slot")
+        rc = lib.gr_beam_attn_slots(ctypes.byref(p), _ptr(slot), _ptr(workspace), ws_bytes, _stream(stream))
+    else:
+        rc = lib.gr_beam_attn(ctypes.byref(p), _ptr(workspace), ws_bytes, _stream(stream))
     if rc != 0:
-        raise GrError(rc, "gr_beam_attn")
+        raise GrError(rc, "gr_beam_attn_slots" if slot is not None else "gr_beam_attn")
     return out, lse_out
+
+
+def gr_beam_attn_slots(q, k_shared, v_shared, cu_seqlens, k_unshared, v_unshared, slot, u, sm_scale, max_L, total_L,
+                       out=None, lse_out=None, workspace=None, stream=None):
+    """gr_beam_attn with the own-token caches read through the slot table `slot` (int32 [B,W,ND]; see gr_beam_slot_update)."""
+    if slot is None:
+        raise ValueError("slot is required")
+    return gr_beam_attn(q, k_shared, v_shared, cu_seqlens, k_unshared, v_unshared, u, sm_scale, max_L, total_L,
+                        out=out, lse_out=lse_out, workspace=workspace, stream=stream, slot=slot)
 
 
 def gr_beam_attn_fp8kv(q, k_shared_fp8, v_shared_fp8, k_scale, v_scale, cu_seqlens, k_unshared, v_unshared, u, sm_scale, max_L, total_L,
@@ -347,6 +365,24 @@ def gr_beam_reorder(parent, k_unshared, v_unshared, u, stream=None):
     rc = lib.gr_beam_reorder(B, W, ND, Hkv, d, int(u), _ptr(parent), _ptr(k_unshared), _ptr(v_unshared), _stream(stream))
     if rc != 0:
         raise GrError(rc, "gr_beam_reorder")
+
+
+def gr_beam_slot_update(parent, slot_in, u, ND, out=None, stream=None):
+    """The slot table after a beam step (nothing in the caches moves): out[b,j,t] = slot_in[b,parent[b,j],t] for t < u,
+    j*ND + t otherwise.  parent int32 [B,W]; slot_in int32 [B,W,ND] or None (identity).  Returns out int32 [B,W,ND]."""
+    import torch
+    lib = load_library()
+    B, W = parent.shape
+    _check(parent, torch.int32, (B, W), "parent")
+    if slot_in is not None:
+        _check(slot_in, torch.int32, (B, W, int(ND)), "slot_in")
+    if out is None:
+        out = _scratch(B * W * int(ND) * 4, parent.device, stream).view(torch.int32).view(B, W, int(ND))
+    _check(out, torch.int32, (B, W, int(ND)), "out")
+    rc = lib.gr_beam_slot_update(B, W, int(ND), int(u), _ptr(parent), _ptr(slot_in), _ptr(out), _stream(stream))
+    if rc != 0:
+        raise GrError(rc, "gr_beam_slot_update")
+    return out
 
 
 def gr_diag_attn_plan(rows_per_workgroup=0, l_segments=0):

@@ -46,6 +46,7 @@ struct AttnCtx {
   float* part_o;    // [B, nsplit, W*Hq, D] fp32, unnormalised
   float* part_ml;   // [B, nsplit, W*Hq, 2] (max in log2 domain, sum)
   const int32_t* order;   // [B] requests by decreasing prompt length, or nullptr (requests taken in index order)
+  const int32_t* slot;    // [B, W, ND] row of the request's own-token block that holds (beam, token), or nullptr (= w * ND + t)
 };
 
 __device__ __forceinline__ float bf16_bits_to_float(uint32_t h) { return __uint_as_float(h << 16); }
@@ -501,6 +502,7 @@ k_beam_attn(AttnCtx c) {
   auto uload = [&](int pass) {                           // 32 rows x D/8 pieces per tensor; a row = PPR consecutive lanes
     const uint16_t* ku_b = c.ku + (size_t)b * c.W * c.ND * c.Hkv * D;      // this request's own-token caches
     const uint16_t* vu_b = c.vu + (size_t)b * c.W * c.ND * c.Hkv * D;
+    const int32_t* slot_b = c.slot ? c.slot + (size_t)b * c.W * c.ND : nullptr;
 #pragma unroll
     for (int i = 0; i < UP; i++) {
       const int pi = lane + 64 * i, row = pi / PPR, col = (pi % PPR) * 8;
@@ -510,7 +512,12 @@ k_beam_attn(AttnCtx c) {
       if (rho < R) {
         int bl, tok;
         divmod_small(rho, c.u, rcp_u, &bl, &tok);
-        const uint32_t off = (uint32_t)(((beam0 + bl) * c.ND + tok) * (c.Hkv * D) + kvh * D + col);
+        int prow = (beam0 + bl) * c.ND + tok;
+        if (slot_b) {                                      // (an entry outside the block falls back to the beam's own row)
+          const int sl = slot_b[prow];
+          prow = ((unsigned)sl < (unsigned)(c.W * c.ND)) ? sl : prow;
+        }
+        const uint32_t off = (uint32_t)(prow * (c.Hkv * D) + kvh * D + col);
         ukp[i] = *(const uint4*)(ku_b + off);
         uvp[i] = *(const uint4*)(vu_b + off);
       }
@@ -943,7 +950,8 @@ extern "C" size_t gr_beam_attn_workspace_bytes(const gr_attn_params* p) {
 }
 
 namespace {
-gr_status attn_run(const gr_attn_params* p, bool kv8, float k_scale, float v_scale, void* workspace, size_t workspace_bytes, void* stream_) {
+gr_status attn_run(const gr_attn_params* p, const int32_t* slot, bool kv8, float k_scale, float v_scale, void* workspace, size_t workspace_bytes,
+                   void* stream_) {
   hipStream_t stream = (hipStream_t)stream_;
   if (!p) return GR_ERR_INVALID_ARG;
   if (kv8 && (!(k_scale > 0.f) || !(k_scale < INFINITY) || !(v_scale > 0.f) || !(v_scale < INFINITY))) return GR_ERR_INVALID_ARG;
@@ -955,7 +963,7 @@ gr_status attn_run(const gr_attn_params* p, bool kv8, float k_scale, float v_sca
   if (p->u > 0 && (!p->k_unshared || !p->v_unshared)) return GR_ERR_INVALID_ARG;
   if (p->Hq % p->Hkv) return GR_ERR_INVALID_ARG;
   if ((((uintptr_t)p->q | (uintptr_t)p->k_shared | (uintptr_t)p->v_shared | (uintptr_t)p->k_unshared | (uintptr_t)p->v_unshared |
-        (uintptr_t)p->out) & 15) || ((uintptr_t)p->cu_seqlens & 3) || ((uintptr_t)p->lse_out & 3))
+        (uintptr_t)p->out) & 15) || ((uintptr_t)p->cu_seqlens & 3) || ((uintptr_t)p->lse_out & 3) || ((uintptr_t)slot & 3))
     return GR_ERR_INVALID_ARG;                                                          // every tensor is moved in 16-byte pieces
   if (!(p->sm_scale > 0.f) || !(p->sm_scale < INFINITY)) return GR_ERR_INVALID_ARG;   // (also rejects NaN: the lazy-maximum test assumes a positive scale)
   if (p->d != 64 && p->d != 128) return GR_ERR_UNSUPPORTED;
@@ -978,7 +986,7 @@ gr_status attn_run(const gr_attn_params* p, bool kv8, float k_scale, float v_sca
   c.q = (const uint16_t*)p->q; c.ks = (const uint16_t*)p->k_shared; c.vs = (const uint16_t*)p->v_shared;
   c.cu = p->cu_seqlens; c.ku = (const uint16_t*)p->k_unshared; c.vu = (const uint16_t*)p->v_unshared;
   c.out = (uint16_t*)p->out; c.lse = p->lse_out;
-  c.part_o = nullptr; c.part_ml = nullptr; c.order = nullptr;
+  c.part_o = nullptr; c.part_ml = nullptr; c.order = nullptr; c.slot = slot;
   const size_t need = gr_beam_attn_workspace_bytes(p);
   if (need > 0) {
     if (!workspace || ((uintptr_t)workspace & 255)) return GR_ERR_INVALID_ARG;
@@ -1027,13 +1035,20 @@ gr_status attn_run(const gr_attn_params* p, bool kv8, float k_scale, float v_sca
 }  // namespace
 
 extern "C" gr_status gr_beam_attn(const gr_attn_params* p, void* workspace, size_t workspace_bytes, void* stream) {
-  return attn_run(p, false, 1.f, 1.f, workspace, workspace_bytes, stream);
+  return attn_run(p, nullptr, false, 1.f, 1.f, workspace, workspace_bytes, stream);
+}
+
+// The same attention with the own-token caches read through a slot table: nothing is moved between decode steps, the
+// table (gr_beam_slot_update) says which row of the request's block holds token t of beam w.
+extern "C" gr_status gr_beam_attn_slots(const gr_attn_params* p, const int32_t* slot, void* workspace, size_t workspace_bytes, void* stream) {
+  if (!slot) return GR_ERR_INVALID_ARG;
+  return attn_run(p, slot, false, 1.f, 1.f, workspace, workspace_bytes, stream);
 }
 
 // The same attention over a prompt cache stored as FP8 E4M3 codes with one scale per tensor.
 extern "C" gr_status gr_beam_attn_fp8kv(const gr_attn_fp8kv_params* p, void* workspace, size_t workspace_bytes, void* stream) {
   if (!p) return GR_ERR_INVALID_ARG;
-  return attn_run(&p->attn, true, p->k_scale, p->v_scale, workspace, workspace_bytes, stream);
+  return attn_run(&p->attn, nullptr, true, p->k_scale, p->v_scale, workspace, workspace_bytes, stream);
 }
 
 // Causal prompt attention through the same kernel (CAUSAL = true).
@@ -1068,7 +1083,7 @@ extern "C" gr_status gr_prefill_attn(const gr_prefill_params* p, void* stream_) 
   c.q = (const uint16_t*)p->q; c.ks = (const uint16_t*)p->k; c.vs = (const uint16_t*)p->v;
   c.cu = p->cu_seqlens; c.ku = nullptr; c.vu = nullptr;
   c.out = (uint16_t*)p->out; c.lse = p->lse_out;
-  c.part_o = nullptr; c.part_ml = nullptr; c.order = nullptr;
+  c.part_o = nullptr; c.part_ml = nullptr; c.order = nullptr; c.slot = nullptr;
   const int64_t groups_padded = ((int64_t)c.n_groups + 7) / 8 * 8;
   const int64_t grid = groups_padded * c.MB;
   if (grid >= ((int64_t)1 << 31)) return GR_ERR_UNSUPPORTED;

@@ -54,7 +54,40 @@ __global__ void __launch_bounds__(kReorderThreads) k_beam_reorder(ReorderCtx c) 
   }
 }
 
+// The slot table of the alternative that moves no cache bytes: token t of beam j is read from row slot[b][j][t] of the
+// request's [W * ND] rows.  After a beam step the new beam j inherits its parent's rows for the tokens both have (t < u)
+// and owns row j * ND + t for the tokens still to come; a dead slot (parent outside [0, W)) owns all of its rows.
+__global__ void __launch_bounds__(256) k_slot_update(int n, int W, int ND, int u, const int32_t* parent, const int32_t* slot_in, int32_t* slot_out) {
+  const int i = blockIdx.x * 256 + threadIdx.x;           // (b, j, t) flattened
+  if (i >= n) return;
+  const int t = i % ND, bj = i / ND, j = bj % W, b = bj / W;
+  int s = j * ND + t;
+  if (t < u) {
+    const int p = parent[bj];
+    if (p >= 0 && p < W) {
+      s = p * ND + t;
+      if (slot_in) {
+        const int sp = slot_in[((size_t)b * W + p) * ND + t];
+        s = ((unsigned)sp < (unsigned)(W * ND)) ? sp : s;
+      }
+    }
+  }
+  slot_out[i] = s;
+}
+
 }  // namespace
+
+extern "C" gr_status gr_beam_slot_update(int32_t B, int32_t W, int32_t ND, int32_t u, const int32_t* parent, const int32_t* slot_in,
+                                         int32_t* slot_out, void* stream_) {
+  if (B <= 0 || W <= 0 || ND <= 0 || u < 0 || u > ND) return GR_ERR_INVALID_ARG;
+  if (!slot_out || slot_in == slot_out || (u > 0 && !parent)) return GR_ERR_INVALID_ARG;
+  const int64_t n = (int64_t)B * W * ND;
+  if (n >= ((int64_t)1 << 31) || (int64_t)W * ND >= ((int64_t)1 << 31)) return GR_ERR_UNSUPPORTED;
+  hipLaunchKernelGGL(k_slot_update, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, (hipStream_t)stream_, (int)n, W, ND, u, parent, slot_in,
+                     slot_out);
+  GR_HIP_TRY(hipGetLastError());
+  return GR_OK;
+}
 
 extern "C" gr_status gr_beam_reorder(int32_t B, int32_t W, int32_t ND, int32_t Hkv, int32_t d, int32_t u,
                                      const int32_t* parent, void* k_unshared, void* v_unshared, void* stream_) {
