@@ -140,3 +140,55 @@ def test_argument_errors(gr):
     assert lib.gr_beam_slot_update(2, 4, 3, 1, None, None, p, None) == -1    # parent missing
     assert lib.gr_beam_attn_slots(None, p, None, 0, None) == -1
     torch.cuda.synchronize()
+
+
+def test_slot_cycle_as_a_graph_replays_to_the_eager_result(gr):
+    """Attention through the table, then the table's update, captured once and replayed with eager work in between."""
+    import torch
+    B, W, Hq, Hkv, d, ND = 2, 24, 8, 2, 128, 3
+    rng = np.random.default_rng(5)
+    a = rand_attn_case(17, B, W, Hq, Hkv, d, ND, ND, (200, 77))
+    cu = a["cu_seqlens"]
+    scale = float(np.float32(1 / np.sqrt(d)))
+    q, ks, vs, d_cu = bf16_to_dev(a["q"]), bf16_to_dev(a["k_shared"]), bf16_to_dev(a["v_shared"]), to_dev(cu)
+    pk, pv = bf16_to_dev(a["k_unshared"]), bf16_to_dev(a["v_unshared"])
+    live = np.ones((B, W), dtype=bool)
+    parents = []
+    for s in range(1, ND):
+        parents.append(_random_parents(rng, B, W, live, n_dead=s))
+        live = parents[-1] >= 0
+    d_par = [to_dev(p) for p in parents]
+    zero_parent = to_dev(np.zeros((B, W), dtype=np.int32))
+    slots = [torch.empty((B, W, ND), dtype=torch.int32, device="cuda:0") for _ in range(2)]
+    outs = [torch.empty((B, W, Hq, d), dtype=torch.bfloat16, device="cuda:0") for _ in range(ND)]
+    ws = torch.empty(max(gr.attn_workspace_bytes(B, W, Hq, Hkv, d, 200), 256), dtype=torch.uint8, device="cuda:0")
+
+    def cycle():
+        gr.gr_beam_slot_update(zero_parent, None, 0, ND, out=slots[0])
+        for s in range(ND):
+            gr.gr_beam_attn_slots(q, ks, vs, d_cu, pk, pv, slots[s & 1], s + 1, scale, 200, 277, out=outs[s], workspace=ws)
+            if s + 1 < ND:
+                gr.gr_beam_slot_update(d_par[s], slots[s & 1], s + 1, ND, out=slots[(s + 1) & 1])
+
+    cycle()
+    torch.cuda.synchronize()
+    want = [o.clone() for o in outs]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        cycle()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        cycle()
+    for rep in range(3):
+        for o in outs:
+            o.zero_()
+        for t in slots:
+            t.fill_(-7)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        for s in range(ND):
+            assert torch.equal(outs[s], want[s]), f"replay {rep}, step {s}"
