@@ -123,3 +123,36 @@ def test_attention_stratified_rows(gr, oracle_lib, config_id):
         assert err <= 2.0 ** -7 * max(1.0, float(np.abs(ref).max()) * 8), f"config {config_id}: {err}"
         np.testing.assert_allclose(lse[tri[:, 0], tri[:, 1], tri[:, 2]], ref_lse, rtol=0, atol=2e-3)
         del a
+
+
+def test_attention_through_a_slot_table_full_size(gr, oracle_lib):
+    """Workload 3 at u = 3 in the launch configuration the benchmark times (256-row workgroups): the own-token rows
+    read through a slot table that sends every (beam, token) to a random beam's row of that token position.  Must be
+    bit-identical to gr_beam_attn over the cache gathered that way, and a stratified sample must match the oracle."""
+    cfg = gr_synth.get_config(3)
+    B, W, ND = cfg.B, cfg.W, cfg.ND
+    cu = gr_synth.make_prompt_lengths(cfg)
+    kv = gr_synth.generate.make_kv_shared(cfg, cu)
+    d_k, d_v, d_cu = bf16_to_dev(kv[0]), bf16_to_dev(kv[1]), to_dev(cu)
+    scale = float(np.float32(1.0 / np.sqrt(cfg.d)))
+    a = gr_synth.make_attention_inputs(cfg, 2, kv_shared=kv)
+    rng = np.random.default_rng(33)
+    src = rng.integers(0, W, size=(B, W, ND)).astype(np.int32)                    # which beam's row holds (b, w, t)
+    slot = (src * ND + np.arange(ND, dtype=np.int32)[None, None, :]).astype(np.int32)
+    bidx = np.arange(B)[:, None, None]
+    tidx = np.arange(ND)[None, None, :]
+    ku_g = np.ascontiguousarray(a["k_unshared"][bidx, src, tidx])                 # the logical cache the table describes
+    vu_g = np.ascontiguousarray(a["v_unshared"][bidx, src, tidx])
+    q = bf16_to_dev(a["q"])
+    max_L, total_L = int(np.diff(cu).max()), int(cu[-1])
+    out_s, _ = gr.gr_beam_attn_slots(q, d_k, d_v, d_cu, bf16_to_dev(a["k_unshared"]), bf16_to_dev(a["v_unshared"]), to_dev(slot),
+                                     3, scale, max_L, total_L)
+    out_g, _ = gr.gr_beam_attn(q, d_k, d_v, d_cu, bf16_to_dev(ku_g), bf16_to_dev(vu_g), 3, scale, max_L, total_L)
+    torch.cuda.synchronize()
+    assert torch.equal(out_s, out_g)
+    tri = _stratified_rows(cfg, rng)
+    print(f"config 3: attention through slots, {len(tri)} rows against the oracle", flush=True)
+    ref, _ = oracle_lib.attn_unified(a["q"], a["k_shared"], a["v_shared"], cu, ku_g, vu_g, 3, scale, tri)
+    got = out_s.float().cpu().numpy()[tri[:, 0], tri[:, 1], tri[:, 2]]
+    err = np.abs(got - ref).max()
+    assert err <= 2e-2, f"max-abs {err}"
